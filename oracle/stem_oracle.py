@@ -1,0 +1,258 @@
+"""CPU oracle for the STEM token-indexed FFN layer — TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 numpy statement of what the layer computes, written from
+the paper's definition of the STEM layer (Method, "STEM", the equation
+y = W_d (SiLU(W_g x) * U[t])) and, for comparison pins, of the SwiGLU FFN
+(Background, first equation) and the additive variant (appendix "STEM-dagger").
+It shares no code with the HIP path and imports nothing from it.  Only
+tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import it;
+the product never routes through it.
+
+The paper prints no backward pass; the gradients below are the chain rule of
+the forward equation and are pinned by finite differences in the tests.  The
+optimiser is AdamW with the paper's stated hyper-parameters (Experiments,
+"Training details" and the hyper-parameter table: weight decay 0.1,
+beta1 0.9, beta2 0.95), applied only to the rows a batch touches.
+
+Every function takes numpy arrays; floating inputs are used as fp64.  No
+intermediate is rounded, except where a function says so (bf16 shadow of the
+table, the residual stream of the stacked decode chain).
+
+Pin status: every function here is pinned by tests/test_oracle_pins.py
+(one-hot matmul forms, finite differences, the dense-SwiGLU invariant, torch's
+AdamW, closed forms, brute force).  Nothing is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# elementary pieces
+# ----------------------------------------------------------------------------
+def sigmoid(z: np.ndarray) -> np.ndarray:
+    """Logistic function 1 / (1 + exp(-z)), evaluated without overflow."""
+    z = np.asarray(z, dtype=np.float64)
+    out = np.empty_like(z)
+    pos = z >= 0
+    out[pos] = 1.0 / (1.0 + np.exp(-z[pos]))
+    ez = np.exp(z[~pos])
+    out[~pos] = ez / (1.0 + ez)
+    return out
+
+
+def silu(z: np.ndarray) -> np.ndarray:
+    """SiLU(z) = z * sigmoid(z), the gate nonlinearity of SwiGLU (Background)."""
+    return np.asarray(z, dtype=np.float64) * sigmoid(z)
+
+
+def silu_prime(z: np.ndarray) -> np.ndarray:
+    """d/dz [z sigmoid(z)] = sigmoid(z) (1 + z (1 - sigmoid(z)))."""
+    s = sigmoid(z)
+    return s * (1.0 + np.asarray(z, dtype=np.float64) * (1.0 - s))
+
+
+def gather_rows(E: np.ndarray, ids: np.ndarray) -> np.ndarray:
+    """U[t] for every token: row ids[i] of the per-layer table (Method, STEM)."""
+    ids = np.asarray(ids)
+    E = np.asarray(E)               # any float storage type; rows are widened on copy
+    V = E.shape[0]
+    if ids.size and (ids.min() < 0 or ids.max() >= V):
+        raise IndexError("token id outside [0, V)")
+    out = np.empty((ids.shape[0], E.shape[1]), dtype=np.float64)
+    for i in range(ids.shape[0]):
+        out[i, :] = E[int(ids[i]), :]
+    return out
+
+
+# ----------------------------------------------------------------------------
+# forward  (Method, STEM equation)
+# ----------------------------------------------------------------------------
+def ffn_forward(x, ids, W_gate, W_down, E):
+    """y_i = W_down (SiLU(W_gate x_i) * E[ids_i]) for every token i.
+
+    x [T,d], ids [T], W_gate [F,d], W_down [d,F], E [V,F].
+    Returns (y [T,d], dict with g, a, u, h [T,F]).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    Wg = np.asarray(W_gate, dtype=np.float64)
+    Wd = np.asarray(W_down, dtype=np.float64)
+    g = x @ Wg.T                      # gate pre-activation  W_g x
+    a = silu(g)                       # SiLU(W_g x)
+    u = gather_rows(E, ids)           # U[t]
+    h = a * u                         # elementwise product
+    y = h @ Wd.T                      # W_d ( . )
+    return y, {"g": g, "a": a, "u": u, "h": h}
+
+
+def swiglu_forward(x, W_gate, W_up, W_down):
+    """Dense SwiGLU FFN  y = W_d (SiLU(W_g x) * (W_u x))  (Background, first equation)."""
+    x = np.asarray(x, dtype=np.float64)
+    g = x @ np.asarray(W_gate, dtype=np.float64).T
+    up = x @ np.asarray(W_up, dtype=np.float64).T
+    return (silu(g) * up) @ np.asarray(W_down, dtype=np.float64).T
+
+
+def stem_dagger_forward(x, ids, W_gate, W_up, W_down, E):
+    """Additive variant  y = W_d (SiLU(W_g x) * (W_u x + U[t]))  (appendix, STEM-dagger)."""
+    x = np.asarray(x, dtype=np.float64)
+    g = x @ np.asarray(W_gate, dtype=np.float64).T
+    up = x @ np.asarray(W_up, dtype=np.float64).T
+    return (silu(g) * (up + gather_rows(E, ids))) @ np.asarray(W_down, dtype=np.float64).T
+
+
+# ----------------------------------------------------------------------------
+# backward  (chain rule of the STEM equation; not printed in the paper)
+# ----------------------------------------------------------------------------
+def ffn_backward(dy, x, ids, W_gate, W_down, E):
+    """Gradients of L = sum_i <y_i, dy_i>.
+
+    Returns dict: dx [T,d], dW_gate [F,d], dW_down [d,F], dU [T,F] (gradient with
+    respect to each token's gathered row), dG [T,F].
+    """
+    dy = np.asarray(dy, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    Wg = np.asarray(W_gate, dtype=np.float64)
+    Wd = np.asarray(W_down, dtype=np.float64)
+    _, f = ffn_forward(x, ids, Wg, Wd, E)
+    dh = dy @ Wd                      # W_d^T dy
+    dU = dh * f["a"]                  # d/du of a*u
+    da = dh * f["u"]                  # d/da of a*u
+    dG = da * silu_prime(f["g"])
+    dx = dG @ Wg                      # W_g^T dg
+    dW_down = dy.T @ f["h"]           # sum_i dy_i h_i^T
+    dW_gate = dG.T @ x                # sum_i dg_i x_i^T
+    return {"dx": dx, "dW_gate": dW_gate, "dW_down": dW_down, "dU": dU, "dG": dG}
+
+
+# ----------------------------------------------------------------------------
+# embedding gradient: sort -> unique -> offsets -> per-row sums
+# ----------------------------------------------------------------------------
+def sort_ids(ids):
+    """Positions ordered by (id ascending, position ascending).
+
+    Returns (sorted_ids [T] int32, perm [T] int32) with sorted_ids[k] = ids[perm[k]].
+    """
+    ids = np.asarray(ids, dtype=np.int64)
+    perm = np.argsort(ids, kind="stable")
+    return ids[perm].astype(np.int32), perm.astype(np.int32)
+
+
+def unique_segments(sorted_ids):
+    """Distinct ids ascending and where each one's run starts in sorted_ids.
+
+    Returns (uniq_ids [U] int32, seg_offsets [U+1] int32), seg_offsets[U] = T.
+    """
+    s = np.asarray(sorted_ids, dtype=np.int64)
+    T = s.shape[0]
+    uniq, offs = [], []
+    for k in range(T):
+        if k == 0 or s[k] != s[k - 1]:
+            uniq.append(int(s[k]))
+            offs.append(k)
+    offs.append(T)
+    return np.asarray(uniq, dtype=np.int32), np.asarray(offs, dtype=np.int32)
+
+
+def embed_grad(ids, dU):
+    """dE[v,:] = sum over tokens i with ids[i] = v of dU[i,:], for touched v only.
+
+    Returns dict: sorted_ids, perm, uniq_ids, seg_offsets, n_uniq and dE_rows [U,F]
+    (row j belongs to table row uniq_ids[j]); rows of the table that no token names
+    have zero gradient and are not represented.
+    """
+    dU = np.asarray(dU, dtype=np.float64)
+    sorted_ids, perm = sort_ids(ids)
+    uniq_ids, seg_offsets = unique_segments(sorted_ids)
+    U = uniq_ids.shape[0]
+    dE_rows = np.zeros((U, dU.shape[1]), dtype=np.float64)
+    for j in range(U):
+        for k in range(int(seg_offsets[j]), int(seg_offsets[j + 1])):
+            dE_rows[j, :] += dU[int(perm[k]), :]
+    return {"sorted_ids": sorted_ids, "perm": perm, "uniq_ids": uniq_ids,
+            "seg_offsets": seg_offsets, "n_uniq": U, "dE_rows": dE_rows}
+
+
+# ----------------------------------------------------------------------------
+# sparse AdamW over touched rows
+# ----------------------------------------------------------------------------
+def bf16_round(a):
+    """Round fp64/fp32 values to the nearest bfloat16 (ties to even); returns fp64.
+
+    Done on the fp32 bit pattern: bfloat16 is the top 16 bits of an IEEE fp32.
+    Values are first rounded to fp32 (the master copy of the table is fp32).
+    """
+    f = np.asarray(a, dtype=np.float32)
+    bits = f.view(np.uint32).astype(np.uint64)
+    lsb = (bits >> np.uint64(16)) & np.uint64(1)
+    rounded = (bits + np.uint64(0x7FFF) + lsb) >> np.uint64(16)
+    out = (rounded << np.uint64(16)).astype(np.uint32).view(np.float32)
+    nan = np.isnan(f)
+    out = np.where(nan, f, out)
+    return out.astype(np.float64)
+
+
+def sparse_adamw(uniq_ids, dE_rows, p, m, v, lr, beta1, beta2, eps, weight_decay, step):
+    """One decoupled-weight-decay Adam step on rows uniq_ids of the table only.
+
+    For a touched row r = uniq_ids[j], element-wise with g = dE_rows[j]:
+        m <- beta1 m + (1-beta1) g ;  v <- beta2 v + (1-beta2) g^2
+        mhat = m / (1-beta1^step) ;   vhat = v / (1-beta2^step)
+        p <- p - lr*wd*p - lr * mhat / (sqrt(vhat) + eps)
+    Rows not named keep p, m, v unchanged (no decay of any kind).  `step` >= 1 is
+    the global step count.  Returns new (p, m, v) as fp64 copies of shape [V,F].
+    """
+    p = np.array(p, dtype=np.float64, copy=True)
+    m = np.array(m, dtype=np.float64, copy=True)
+    v = np.array(v, dtype=np.float64, copy=True)
+    g_all = np.asarray(dE_rows, dtype=np.float64)
+    c1 = 1.0 - beta1 ** step
+    c2 = 1.0 - beta2 ** step
+    for j, r in enumerate(np.asarray(uniq_ids)):
+        r = int(r)
+        g = g_all[j]
+        m[r] = beta1 * m[r] + (1.0 - beta1) * g
+        v[r] = beta2 * v[r] + (1.0 - beta2) * g * g
+        mhat = m[r] / c1
+        vhat = v[r] / c2
+        p[r] = p[r] - lr * weight_decay * p[r] - lr * mhat / (np.sqrt(vhat) + eps)
+    return p, m, v
+
+
+def sparse_adamw_rows(dE_rows, p_rows, m_rows, v_rows, lr, beta1, beta2, eps, weight_decay, step):
+    """Same update as sparse_adamw, on already-gathered rows (for large tables,
+    where only the touched rows are brought to the host).  Returns (p, m, v) rows."""
+    U = np.asarray(dE_rows).shape[0]
+    return sparse_adamw(np.arange(U), dE_rows, p_rows, m_rows, v_rows,
+                        lr, beta1, beta2, eps, weight_decay, step)
+
+
+# ----------------------------------------------------------------------------
+# host-resident table: token de-duplication for prefetch (System Implementation)
+# ----------------------------------------------------------------------------
+def dedup_remap(ids):
+    """Distinct ids ascending and, per token, the slot of its id in that list."""
+    ids = np.asarray(ids, dtype=np.int64)
+    uniq = sorted(set(int(t) for t in ids))
+    slot = {t: j for j, t in enumerate(uniq)}
+    remap = np.asarray([slot[int(t)] for t in ids], dtype=np.int32)
+    return np.asarray(uniq, dtype=np.int32), remap
+
+
+# ----------------------------------------------------------------------------
+# stacked decode chain (several STEM layers joined by a residual stream)
+# ----------------------------------------------------------------------------
+def decode_chain(x0, ids, layers, round_stream=bf16_round):
+    """x_{l+1} = round(x_l + y_l), y_l = STEM layer l applied to x_l, same ids at
+    every layer (the table is indexed by token id, one vector per id per layer).
+    `layers` is a list of (W_gate, W_down, E).  The residual stream is rounded to
+    the storage type between layers, as the harness stores it; nothing else is.
+    Returns the list [x_1, ..., x_N].
+    """
+    x = np.asarray(x0, dtype=np.float64)
+    outs = []
+    for (Wg, Wd, E) in layers:
+        y, _ = ffn_forward(x, ids, Wg, Wd, E)
+        x = round_stream(x + y)
+        outs.append(x)
+    return outs

@@ -1,0 +1,353 @@
+"""Pins for the CPU oracle: each check compares it with something other than
+itself — a one-hot matmul, finite differences, a library routine (torch's SiLU,
+linear and AdamW, scipy's expit, numpy's unique), a closed form or brute force.
+All CPU, all tiny.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import stem_oracle as O
+from paper_2601_10639_amd import inputs
+
+
+def _tiny(seed=0, T=12, d=8, F=16, V=11, scale=0.5):
+    rng = np.random.default_rng(seed)
+    x = rng.normal(size=(T, d))
+    Wg = rng.normal(size=(F, d)) * scale
+    Wd = rng.normal(size=(d, F)) * scale
+    E = rng.normal(size=(V, F))
+    ids = rng.integers(0, V, size=T).astype(np.int32)
+    ids[3] = ids[0]  # make sure at least one id repeats
+    r = rng.normal(size=(T, d))
+    return x, ids, Wg, Wd, E, r
+
+
+def _onehot(ids, V):
+    P = np.zeros((len(ids), V))
+    P[np.arange(len(ids)), ids] = 1.0
+    return P
+
+
+# -- elementary --------------------------------------------------------------
+def test_sigmoid_matches_scipy_expit():
+    z = np.concatenate([np.linspace(-50, 50, 2001), [-800.0, 800.0, 0.0]])
+    np.testing.assert_allclose(O.sigmoid(z), scipy.special.expit(z), rtol=1e-15, atol=0)
+
+
+def test_silu_matches_torch():
+    z = np.linspace(-20, 20, 1001)
+    ref = torch.nn.functional.silu(torch.from_numpy(z)).numpy()
+    np.testing.assert_allclose(O.silu(z), ref, rtol=1e-14, atol=1e-300)
+
+
+def test_silu_prime_is_derivative_of_silu():
+    z = np.linspace(-8, 8, 321)
+    h = 1e-5
+    fd = (O.silu(z + h) - O.silu(z - h)) / (2 * h)
+    np.testing.assert_allclose(O.silu_prime(z), fd, rtol=0, atol=1e-8)
+    ref = torch.from_numpy(z).requires_grad_()
+    torch.nn.functional.silu(ref).sum().backward()
+    np.testing.assert_allclose(O.silu_prime(z), ref.grad.numpy(), rtol=1e-13, atol=1e-15)
+
+
+# -- gather and forward ------------------------------------------------------
+def test_gather_is_onehot_matmul():
+    x, ids, Wg, Wd, E, r = _tiny()
+    np.testing.assert_array_equal(O.gather_rows(E, ids), _onehot(ids, E.shape[0]) @ E)
+
+
+def test_gather_rejects_out_of_range():
+    _, ids, _, _, E, _ = _tiny()
+    bad = ids.copy(); bad[0] = E.shape[0]
+    with pytest.raises(IndexError):
+        O.gather_rows(E, bad)
+    bad[0] = -1
+    with pytest.raises(IndexError):
+        O.gather_rows(E, bad)
+
+
+def test_forward_scalar_closed_form():
+    # d = F = 1:  y = w_d * (w_g x) * sigmoid(w_g x) * e
+    wg, wd, e, x = 0.7, -1.3, 2.5, 0.9
+    y, _ = O.ffn_forward([[x]], [0], [[wg]], [[wd]], [[e]])
+    z = wg * x
+    assert y.shape == (1, 1)
+    assert y[0, 0] == pytest.approx(wd * z / (1 + np.exp(-z)) * e, rel=1e-15)
+
+
+def test_forward_reduces_to_dense_swiglu_on_constant_input():
+    # If every token carries the same hidden state c and every table row equals
+    # W_up c, the STEM layer is the SwiGLU FFN on c.  The SwiGLU side is written
+    # with torch's library routines, not with the oracle.
+    rng = np.random.default_rng(3)
+    T, d, F, V = 7, 6, 10, 5
+    c = rng.normal(size=d)
+    Wg, Wu, Wd = rng.normal(size=(F, d)), rng.normal(size=(F, d)), rng.normal(size=(d, F))
+    E = np.tile(Wu @ c, (V, 1))
+    ids = rng.integers(0, V, size=T)
+    x = np.tile(c, (T, 1))
+    y, _ = O.ffn_forward(x, ids, Wg, Wd, E)
+    tc = torch.from_numpy(c)
+    lin = torch.nn.functional.linear
+    ref = lin(torch.nn.functional.silu(lin(tc, torch.from_numpy(Wg))) * lin(tc, torch.from_numpy(Wu)),
+              torch.from_numpy(Wd)).numpy()
+    np.testing.assert_allclose(y, np.tile(ref, (T, 1)), rtol=1e-12, atol=1e-13)
+    # and the oracle's own dense SwiGLU agrees with the same library expression
+    np.testing.assert_allclose(O.swiglu_forward(x, Wg, Wu, Wd), np.tile(ref, (T, 1)), rtol=1e-12, atol=1e-13)
+
+
+def test_forward_against_per_token_loops():
+    # brute force: scalar loops straight from the layer's equation
+    x, ids, Wg, Wd, E, _ = _tiny(seed=5, T=5, d=3, F=4, V=6)
+    y, _ = O.ffn_forward(x, ids, Wg, Wd, E)
+    for i in range(x.shape[0]):
+        h = []
+        for f in range(Wg.shape[0]):
+            z = sum(Wg[f, k] * x[i, k] for k in range(x.shape[1]))
+            h.append(z / (1.0 + np.exp(-z)) * E[ids[i], f])
+        for a in range(Wd.shape[0]):
+            want = sum(Wd[a, f] * h[f] for f in range(len(h)))
+            assert y[i, a] == pytest.approx(want, rel=1e-12, abs=1e-14)
+
+
+def test_forward_linear_in_table_and_zero_row():
+    x, ids, Wg, Wd, E, _ = _tiny(seed=1)
+    E2 = np.random.default_rng(9).normal(size=E.shape)
+    y1, _ = O.ffn_forward(x, ids, Wg, Wd, E)
+    y2, _ = O.ffn_forward(x, ids, Wg, Wd, E2)
+    y12, _ = O.ffn_forward(x, ids, Wg, Wd, 2.0 * E - 3.0 * E2)
+    np.testing.assert_allclose(y12, 2.0 * y1 - 3.0 * y2, rtol=1e-12, atol=1e-12)
+    Ez = E.copy(); Ez[ids[0]] = 0.0
+    yz, _ = O.ffn_forward(x, ids, Wg, Wd, Ez)
+    assert np.all(yz[ids == ids[0]] == 0.0)
+    np.testing.assert_array_equal(yz[ids != ids[0]], y1[ids != ids[0]])
+
+
+def test_forward_token_permutation_equivariance():
+    x, ids, Wg, Wd, E, _ = _tiny(seed=2)
+    perm = np.random.default_rng(4).permutation(len(ids))
+    y, _ = O.ffn_forward(x, ids, Wg, Wd, E)
+    yp, _ = O.ffn_forward(x[perm], ids[perm], Wg, Wd, E)
+    np.testing.assert_array_equal(yp, y[perm])
+
+
+def test_stem_dagger_special_cases():
+    # zero up-projection -> the STEM layer; zero table -> the dense SwiGLU FFN
+    x, ids, Wg, Wd, E, _ = _tiny(seed=6)
+    Wu = np.random.default_rng(7).normal(size=Wg.shape)
+    y_stem, _ = O.ffn_forward(x, ids, Wg, Wd, E)
+    np.testing.assert_array_equal(O.stem_dagger_forward(x, ids, Wg, np.zeros_like(Wu), Wd, E), y_stem)
+    np.testing.assert_array_equal(O.stem_dagger_forward(x, ids, Wg, Wu, Wd, np.zeros_like(E)),
+                                  O.swiglu_forward(x, Wg, Wu, Wd))
+    both = O.stem_dagger_forward(x, ids, Wg, Wu, Wd, E)
+    np.testing.assert_allclose(both, y_stem + O.swiglu_forward(x, Wg, Wu, Wd), rtol=1e-12, atol=1e-12)
+
+
+# -- backward ----------------------------------------------------------------
+def _loss(x, ids, Wg, Wd, E, r):
+    y, _ = O.ffn_forward(x, ids, Wg, Wd, E)
+    return float((y * r).sum())
+
+
+@pytest.mark.parametrize("which", ["x", "W_gate", "W_down", "E"])
+def test_backward_matches_central_finite_differences(which):
+    x, ids, Wg, Wd, E, r = _tiny(seed=11, T=9, d=5, F=7, V=6)
+    grads = O.ffn_backward(r, x, ids, Wg, Wd, E)
+    eg = O.embed_grad(ids, grads["dU"])
+    dE = np.zeros_like(E)
+    dE[eg["uniq_ids"]] = eg["dE_rows"]
+    analytic = {"x": grads["dx"], "W_gate": grads["dW_gate"], "W_down": grads["dW_down"], "E": dE}[which]
+    params = {"x": x, "W_gate": Wg, "W_down": Wd, "E": E}
+    target = params[which]
+    h = 1e-6
+    fd = np.zeros_like(target)
+    for idx in itertools.product(*[range(n) for n in target.shape]):
+        old = target[idx]
+        target[idx] = old + h
+        lp = _loss(params["x"], ids, params["W_gate"], params["W_down"], params["E"], r)
+        target[idx] = old - h
+        lm = _loss(params["x"], ids, params["W_gate"], params["W_down"], params["E"], r)
+        target[idx] = old
+        fd[idx] = (lp - lm) / (2 * h)
+    scale = np.abs(fd).max()
+    assert scale > 0
+    assert np.abs(analytic - fd).max() / scale < 1e-7
+
+
+def test_backward_against_torch_autograd():
+    x, ids, Wg, Wd, E, r = _tiny(seed=12)
+    tx, tWg, tWd, tE = (torch.from_numpy(a.copy()).requires_grad_() for a in (x, Wg, Wd, E))
+    u = torch.nn.functional.embedding(torch.from_numpy(ids.astype(np.int64)), tE)
+    y = torch.nn.functional.linear(torch.nn.functional.silu(torch.nn.functional.linear(tx, tWg)) * u, tWd)
+    (y * torch.from_numpy(r)).sum().backward()
+    g = O.ffn_backward(r, x, ids, Wg, Wd, E)
+    np.testing.assert_allclose(g["dx"], tx.grad.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(g["dW_gate"], tWg.grad.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(g["dW_down"], tWd.grad.numpy(), rtol=1e-11, atol=1e-12)
+    eg = O.embed_grad(ids, g["dU"])
+    dE = np.zeros_like(E); dE[eg["uniq_ids"]] = eg["dE_rows"]
+    np.testing.assert_allclose(dE, tE.grad.numpy(), rtol=1e-11, atol=1e-12)
+
+
+# -- embedding gradient ------------------------------------------------------
+def test_embed_grad_is_onehot_transpose_matmul():
+    x, ids, Wg, Wd, E, r = _tiny(seed=13)
+    dU = O.ffn_backward(r, x, ids, Wg, Wd, E)["dU"]
+    eg = O.embed_grad(ids, dU)
+    dense = _onehot(ids, E.shape[0]).T @ dU
+    touched = np.zeros(E.shape[0], bool); touched[eg["uniq_ids"]] = True
+    np.testing.assert_allclose(eg["dE_rows"], dense[eg["uniq_ids"]], rtol=1e-13, atol=1e-14)
+    assert np.all(dense[~touched] == 0.0)
+    assert set(eg["uniq_ids"].tolist()) == set(ids.tolist())
+
+
+def test_embed_grad_all_equal_and_all_distinct():
+    rng = np.random.default_rng(14)
+    dU = rng.normal(size=(10, 6))
+    eg = O.embed_grad(np.full(10, 4, np.int32), dU)
+    assert eg["n_uniq"] == 1 and eg["uniq_ids"].tolist() == [4] and eg["seg_offsets"].tolist() == [0, 10]
+    np.testing.assert_allclose(eg["dE_rows"][0], dU.sum(axis=0), rtol=1e-14)
+    ids = rng.permutation(10).astype(np.int32)
+    eg = O.embed_grad(ids, dU)
+    assert eg["n_uniq"] == 10 and eg["uniq_ids"].tolist() == list(range(10))
+    np.testing.assert_array_equal(eg["dE_rows"], dU[np.argsort(ids)])
+
+
+def test_sort_and_segments_brute_force_and_invariants():
+    rng = np.random.default_rng(15)
+    for T, V in [(1, 1), (1, 9), (17, 3), (64, 1000), (200, 7)]:
+        ids = rng.integers(0, V, size=T).astype(np.int32)
+        s, perm = O.sort_ids(ids)
+        want = sorted((int(t), i) for i, t in enumerate(ids))
+        assert s.tolist() == [t for t, _ in want]
+        assert perm.tolist() == [i for _, i in want]
+        assert sorted(perm.tolist()) == list(range(T))
+        uniq, offs = O.unique_segments(s)
+        assert uniq.tolist() == sorted(set(ids.tolist()))
+        assert offs[0] == 0 and offs[-1] == T and np.all(np.diff(offs) > 0)
+        counts = np.bincount(ids, minlength=V)
+        assert np.diff(offs).tolist() == counts[uniq].tolist()
+        for j, t in enumerate(uniq):
+            assert np.all(s[offs[j]:offs[j + 1]] == t)
+    # empty input
+    s, perm = O.sort_ids(np.zeros(0, np.int32))
+    uniq, offs = O.unique_segments(s)
+    assert s.size == 0 and perm.size == 0 and uniq.size == 0 and offs.tolist() == [0]
+
+
+def test_embed_grad_column_sum_conservation():
+    rng = np.random.default_rng(16)
+    ids = inputs.zipf_ids(300, 50, seed=1)
+    dU = rng.normal(size=(300, 5))
+    eg = O.embed_grad(ids, dU)
+    np.testing.assert_allclose(eg["dE_rows"].sum(axis=0), dU.sum(axis=0), rtol=1e-12)
+
+
+# -- AdamW -------------------------------------------------------------------
+HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+
+
+def test_adamw_all_rows_touched_equals_torch_adamw():
+    rng = np.random.default_rng(17)
+    V, F = 6, 5
+    p0 = rng.normal(size=(V, F))
+    tp = torch.from_numpy(p0.copy()).requires_grad_()
+    opt = torch.optim.AdamW([tp], lr=HP["lr"], betas=(HP["beta1"], HP["beta2"]), eps=HP["eps"],
+                            weight_decay=HP["weight_decay"])
+    p, m, v = p0, np.zeros((V, F)), np.zeros((V, F))
+    for step in range(1, 5):
+        g = rng.normal(size=(V, F)) * (10.0 ** rng.integers(-3, 2))
+        tp.grad = torch.from_numpy(g.copy())
+        opt.step()
+        p, m, v = O.sparse_adamw(np.arange(V), g, p, m, v, step=step, **HP)
+        np.testing.assert_allclose(p, tp.detach().numpy(), rtol=1e-12, atol=1e-15)
+        st = opt.state[tp]
+        np.testing.assert_allclose(m, st["exp_avg"].numpy(), rtol=1e-12, atol=1e-18)
+        np.testing.assert_allclose(v, st["exp_avg_sq"].numpy(), rtol=1e-12, atol=1e-18)
+
+
+def test_adamw_step_one_closed_form_and_untouched_rows():
+    rng = np.random.default_rng(18)
+    V, F = 9, 4
+    p0 = rng.normal(size=(V, F)); m0 = np.zeros((V, F)); v0 = np.zeros((V, F))
+    uniq = np.array([1, 4, 7], np.int32)
+    g = rng.normal(size=(3, F))
+    p, m, v = O.sparse_adamw(uniq, g, p0, m0, v0, step=1, **HP)
+    want = p0[uniq] * (1 - HP["lr"] * HP["weight_decay"]) - HP["lr"] * g / (np.abs(g) + HP["eps"])
+    np.testing.assert_allclose(p[uniq], want, rtol=1e-12)
+    rest = np.setdiff1d(np.arange(V), uniq)
+    np.testing.assert_array_equal(p[rest], p0[rest])
+    assert np.all(m[rest] == 0) and np.all(v[rest] == 0)
+    # a touched row with zero gradient still decays its weight and moments
+    m1 = rng.normal(size=(V, F)); v1 = rng.random(size=(V, F))
+    p2, m2, v2 = O.sparse_adamw(np.array([2]), np.zeros((1, F)), p0, m1, v1, step=3, **HP)
+    np.testing.assert_allclose(m2[2], HP["beta1"] * m1[2], rtol=1e-15)
+    np.testing.assert_allclose(v2[2], HP["beta2"] * v1[2], rtol=1e-15)
+    assert not np.array_equal(p2[2], p0[2])
+
+
+def test_adamw_rows_form_equals_table_form():
+    rng = np.random.default_rng(19)
+    V, F = 8, 3
+    p0, m0, v0 = rng.normal(size=(V, F)), rng.normal(size=(V, F)), rng.random(size=(V, F))
+    uniq = np.array([0, 3, 6]); g = rng.normal(size=(3, F))
+    p, m, v = O.sparse_adamw(uniq, g, p0, m0, v0, step=5, **HP)
+    pr, mr, vr = O.sparse_adamw_rows(g, p0[uniq], m0[uniq], v0[uniq], step=5, **HP)
+    np.testing.assert_array_equal(pr, p[uniq]); np.testing.assert_array_equal(mr, m[uniq])
+    np.testing.assert_array_equal(vr, v[uniq])
+
+
+def test_bf16_round_matches_torch():
+    rng = np.random.default_rng(20)
+    a = np.concatenate([rng.normal(size=5000), rng.normal(size=2000) * 1e-30, rng.normal(size=2000) * 1e30,
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.0e38, np.inf, -np.inf]]).astype(np.float32)
+    # exact ties: mantissa low half == 0x8000
+    ties = (rng.integers(0, 2 ** 15, size=2000).astype(np.uint32) << np.uint32(16) | np.uint32(0x8000)).view(np.float32)
+    ties = ties[np.isfinite(ties)]
+    a = np.concatenate([a, ties])
+    ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.bf16_round(a), ref)
+
+
+# -- prefetch dedup and decode chain ------------------------------------------
+def test_dedup_remap_matches_numpy_unique():
+    ids = inputs.zipf_ids(500, 97, seed=3)
+    uniq, remap = O.dedup_remap(ids)
+    u2, inv = np.unique(ids, return_inverse=True)
+    np.testing.assert_array_equal(uniq, u2)
+    np.testing.assert_array_equal(remap, inv)
+    np.testing.assert_array_equal(uniq[remap], ids)
+
+
+def test_decode_chain_composes_layers_with_rounded_residual():
+    rng = np.random.default_rng(21)
+    T, d, F, V = 4, 8, 16, 5
+    ids = rng.integers(0, V, size=T)
+    layers = [(rng.normal(size=(F, d)) * .3, rng.normal(size=(d, F)) * .3, rng.normal(size=(V, F))) for _ in range(3)]
+    x0 = O.bf16_round(rng.normal(size=(T, d)))
+    outs = O.decode_chain(x0, ids, layers)
+    x = x0
+    for l, (Wg, Wd, E) in enumerate(layers):
+        y, _ = O.ffn_forward(x, ids, Wg, Wd, E)
+        x = torch.from_numpy((x + y).astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+        np.testing.assert_array_equal(outs[l], x)
+
+
+# -- input generators ----------------------------------------------------------
+def test_zipf_ids_follow_the_power_law():
+    V, n = 1000, 200000
+    ids = inputs.zipf_ids(n, V, seed=5, permute=False)
+    assert ids.dtype == np.int32 and ids.min() >= 0 and ids.max() < V
+    w = np.arange(1, V + 1, dtype=np.float64) ** -1.1
+    p = w / w.sum()
+    freq = np.bincount(ids, minlength=V) / n
+    assert abs(freq[0] - p[0]) < 5 * np.sqrt(p[0] * (1 - p[0]) / n)
+    assert abs(freq[:10].sum() - p[:10].sum()) < 0.01
+    # the permuted stream has the same multiset of frequencies
+    idp = inputs.zipf_ids(n, V, seed=5, permute=True)
+    assert sorted(np.bincount(idp, minlength=V).tolist()) == sorted(np.bincount(ids, minlength=V).tolist())
+    np.testing.assert_array_equal(inputs.zipf_ids(100, V, seed=5), inputs.zipf_ids(100, V, seed=5))
