@@ -1,0 +1,173 @@
+/*
+ * libstem — the STEM token-indexed FFN layer on one MI355X (gfx950), C ABI.
+ *
+ * The layer (paper: Method, "STEM", the layer equation) replaces the up-projection
+ * of a SwiGLU FFN by a row of a per-layer table indexed by the token id:
+ *
+ *     y_i = W_down ( SiLU(W_gate x_i) * E[ids_i] )          for every token i
+ *
+ * with W_gate [F,d], W_down [d,F] (the paper's shapes, Background) and the table
+ * E [V,F] ("U_l in R^{V x d_ff}").  Token ids are 0-based here (the paper counts
+ * from 1).  No bias, norm or residual is part of the layer.
+ *
+ * Conventions for every call
+ *   - All matrices are row-major and dense (leading dimension = number of columns).
+ *   - Unless a parameter says "host", every pointer is DEVICE memory owned by the
+ *     caller, 16-byte aligned, valid until the work enqueued on `stream` has run.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work and return; they do not synchronise unless stated.
+ *   - Element type of activations, weights and the table is the context's dtype
+ *     (STEM_BF16: bfloat16 storage, fp32 accumulation and epilogue math;
+ *      STEM_F32: fp32 throughout).  Weight gradients, table-row gradients and
+ *     optimiser state are always fp32.
+ *   - d_model and d_ff must be multiples of 64 for STEM_BF16 and of 4 for STEM_F32;
+ *     T may be any value in [0, max_tokens].  T == 0 is a no-op that returns STEM_OK.
+ *   - Errors: argument and shape errors are detected on the host before anything
+ *     is launched and returned as a status; stem_last_error() gives the text.
+ *     Token ids outside [0, E_rows) never cause an out-of-bounds access: kernels
+ *     clamp them to a valid row and raise a sticky flag that the next libstem call
+ *     on the context (or stem_sync_status) reports as STEM_ERR_ID_RANGE; results
+ *     computed from such ids are unspecified.
+ *   - The context owns only scratch memory (sort buffers, partial sums, the
+ *     internal H and dG buffers, pinned staging, one side stream and its events),
+ *     all sized by stem_create from max_tokens; no call allocates.
+ *     Calls on one context must not overlap in time (they share that scratch).
+ */
+#ifndef STEM_H
+#define STEM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct stem_ctx stem_ctx; /* opaque */
+
+typedef enum {
+  STEM_OK = 0,
+  STEM_ERR_INVALID_ARG = 1, /* null pointer, bad enum, misaligned pointer            */
+  STEM_ERR_SHAPE = 2,       /* negative size, T > max_tokens, E_rows < 1, ...        */
+  STEM_ERR_ID_RANGE = 3,    /* a token id outside [0, E_rows) was seen by a kernel   */
+  STEM_ERR_WORKSPACE = 4,   /* a caller-provided capacity is too small               */
+  STEM_ERR_UNSUPPORTED = 5, /* d_model / d_ff not a supported multiple               */
+  STEM_ERR_HIP = 6          /* a HIP runtime call failed; see stem_last_error        */
+} stem_status;
+
+typedef enum { STEM_F32 = 0, STEM_BF16 = 1 } stem_dtype;
+
+typedef struct {
+  int32_t d_model; /* d   */
+  int32_t d_ff;    /* F   */
+  int32_t vocab;   /* V: number of rows of a device-resident table (upper bound on ids) */
+  int32_t dtype;   /* stem_dtype */
+} stem_layer_desc;
+
+/* AdamW hyper-parameters (paper, Experiments: weight decay 0.1, beta1 0.9, beta2 0.95;
+ * eps is not given there, 1e-8 is the customary value).  step >= 1 is the global step. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  int64_t step;
+} stem_adamw_hparams;
+
+/* ---- context ------------------------------------------------------------------- */
+
+/* Creates a context on HIP device `device` with scratch for calls of up to max_tokens
+ * tokens.  *out is NULL on failure.  host pointers: out, desc. */
+stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max_tokens, int device);
+/* Synchronises the device and frees the context's scratch.  NULL is allowed. */
+void stem_destroy(stem_ctx* ctx);
+/* Text of the last error on this context (or of the last failed stem_create when
+ * ctx is NULL).  Never NULL; valid until the next call on the context. */
+const char* stem_last_error(const stem_ctx* ctx);
+const char* stem_status_string(stem_status s);
+/* Waits for `stream`, then reports and clears the sticky id-range flag. */
+stem_status stem_sync_status(stem_ctx* ctx, void* stream);
+
+/* ---- the layer (Method, STEM layer equation) ---------------------------------- */
+
+/* Forward.  x [T,d], ids [T] int32, W_gate [F,d], W_down [d,F], E [E_rows,F], y [T,d].
+ * G = x W_gate^T;  H = SiLU(G) * E[ids];  y = H W_down^T.
+ * save_G, save_H: [T,F] in the context dtype, or NULL (inference) — what backward needs.
+ * wait_event: NULL, or a hipEvent_t (as returned by stem_prefetch_rows) that marks E's
+ * rows as ready.  When given, the gate GEMM is enqueued first, `stream` then waits on
+ * the event, and the SiLU*gather runs as a separate kernel before the down GEMM, so
+ * the row copy overlaps the gate GEMM.  When NULL the gather is fused into the gate
+ * GEMM's epilogue. */
+stem_status stem_ffn_forward(stem_ctx* ctx, const void* x, const int32_t* ids, const void* W_gate,
+                             const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y,
+                             void* save_G, void* save_H, void* wait_event, void* stream);
+
+/* Backward of L = sum_i <y_i, dy_i> (chain rule of the layer equation; the paper
+ * prints none).  dy [T,d]; saved_G [T,F] as written by forward (required); saved_H
+ * [T,F] or NULL (then H is recomputed from saved_G and E).
+ *   dH = dy W_down ;  dU = dH * SiLU(G) ;  dG = dH * E[ids] * SiLU'(G)
+ *   dx = dG W_gate ;  dW_down = dy^T H ;  dW_gate = dG^T x
+ * Outputs: dx [T,d] (context dtype), dW_gate [F,d] fp32, dW_down [d,F] fp32 (overwritten
+ * when accumulate == 0, added to otherwise), dU [T,F] (context dtype) = gradient with
+ * respect to each token's gathered row, the input of stem_embed_grad.  dx may be NULL
+ * (then the dx GEMM is skipped). */
+stem_status stem_ffn_backward(stem_ctx* ctx, const void* dy, const void* x, const int32_t* ids,
+                              const void* W_gate, const void* W_down, const void* E, int64_t E_rows,
+                              const void* saved_G, const void* saved_H, int64_t T, void* dx,
+                              float* dW_gate, float* dW_down, void* dU, int accumulate, void* stream);
+
+/* ---- table gradient: only the touched rows (System Implementation: token
+ *      de-duplication; gradients of the table rows go to the optimiser) ---------- */
+
+/* Stable sort of (ids[i], i) by id, distinct ids with their run offsets, and the
+ * per-row sums  dE_rows[j,:] = sum_{k in [seg_offsets[j], seg_offsets[j+1])} dU[perm[k],:]
+ * added in a fixed order (bit-identical on every run; no floating-point atomics).
+ * Outputs (device): sorted_ids [T], perm [T], uniq_ids [min(T,V)] ascending,
+ * seg_offsets [min(T,V)+1] (seg_offsets[n_uniq] = T), n_uniq [1], dE_rows
+ * [min(T,V), F] fp32 of which rows [0, n_uniq) are written.  dU is [T,F] in the context
+ * dtype.  dE_rows and dU may both be NULL to run only the integer part. */
+stem_status stem_embed_grad(stem_ctx* ctx, const int32_t* ids, const void* dU, int64_t T,
+                            int32_t* sorted_ids, int32_t* perm, int32_t* uniq_ids,
+                            int32_t* seg_offsets, int32_t* n_uniq, float* dE_rows, void* stream);
+
+/* ---- optimiser: AdamW on the touched rows only --------------------------------- */
+
+/* For each j < *n_uniq, row r = uniq_ids[j], element-wise with g = dE_rows[j]:
+ *   m <- b1 m + (1-b1) g ;  v <- b2 v + (1-b2) g^2
+ *   p <- p - lr*wd*p - lr * (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps)
+ * p is master[r] (fp32).  For STEM_BF16, E[r] receives p rounded to nearest-even
+ * bfloat16; for STEM_F32 `master` may be NULL and E itself is p.  m, v [V,F] fp32.
+ * Rows not listed are not read or written.  uniq_ids, n_uniq: device, as produced by
+ * stem_embed_grad; max_rows = capacity of uniq_ids / dE_rows (rows).  hp: host. */
+stem_status stem_embed_sparse_adamw(stem_ctx* ctx, const int32_t* uniq_ids, const int32_t* n_uniq,
+                                    int64_t max_rows, const float* dE_rows, void* E, float* master,
+                                    float* m, float* v, const stem_adamw_hparams* hp, void* stream);
+
+/* ---- host-resident table (System Implementation: CPU offloading, asynchronous
+ *      prefetch, token de-duplication) ------------------------------------------- */
+
+/* E_host [V,F] lives in pinned host memory (hipHostMalloc); ids_host [T] is host memory.
+ * De-duplicates ids on the host (distinct ids ascending), copies row uniq[j] of E_host to
+ * E_compact[j] (device, capacity `cap` rows) on the context's side stream, and writes
+ * remap[i] = j with uniq[j] == ids[i] (device [T]) there too, so that
+ *   stem_ffn_forward(E = E_compact, ids = remap, E_rows = *n_uniq_host, wait_event = *ready_event)
+ * is the same layer.  *n_uniq_host (host) is valid on return; uniq_ids_host (host, may be
+ * NULL, capacity cap) receives the distinct ids.  *ready_event is a hipEvent_t owned by
+ * the context, recorded after the copies, valid until the next stem_prefetch_rows call.
+ * Returns STEM_ERR_WORKSPACE if there are more than cap distinct ids, STEM_ERR_ID_RANGE if
+ * an id is outside [0, V).  Blocks only for the host-side de-duplication. */
+stem_status stem_prefetch_rows(stem_ctx* ctx, const void* E_host, const int32_t* ids_host, int64_t T,
+                               void* E_compact, int64_t cap, int32_t* remap, int64_t* n_uniq_host,
+                               int32_t* uniq_ids_host, void** ready_event);
+
+/* ---- measurement aid ------------------------------------------------------------ */
+
+/* With profiling on, every kernel launch of the context is bracketed by HIP events on
+ * the launch stream.  stem_profile_read synchronises the device, adds the elapsed time
+ * of every recorded launch to per-kernel totals, and returns kernel `k`'s name, total
+ * milliseconds and launch count (k in [0, stem_profile_kernels())).  Reset clears totals. */
+stem_status stem_profile_enable(stem_ctx* ctx, int on);
+int stem_profile_kernels(void);
+stem_status stem_profile_read(stem_ctx* ctx, int k, const char** name, double* total_ms, int64_t* launches);
+stem_status stem_profile_reset(stem_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STEM_H */

@@ -1,0 +1,480 @@
+// libstem C ABI: argument checks, the context's scratch, and the launch sequences of
+// the STEM layer's forward, backward, table-gradient, optimiser and prefetch calls.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <thread>
+#include <vector>
+
+#include "stem_internal.h"
+
+namespace {
+
+char g_create_err[512] = "";
+
+const char* const kKernelNames[K_COUNT_] = {
+    "gemm_gate_fused", "gemm_gate_plain", "gemm_down",    "gemm_dh_fused", "gemm_dx",      "gemm_dw_down",
+    "gemm_dw_gate",    "silu_gather",     "dh_epilogue",  "sort_count",    "sort_scan",    "sort_scatter",
+    "sort_fused",      "unique",          "seg_reduce",   "seg_combine",   "sparse_adamw", "row_copy"};
+
+stem_status fail(stem_ctx* c, stem_status st, const char* fmt, ...) {
+  char* buf = c ? c->err : g_create_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, 512, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+#define HIP_TRY(c, expr)                                                                     \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return fail((c), STEM_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_),  \
+                  __FILE__, __LINE__);                                                       \
+  } while (0)
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline size_t esize(const stem_ctx* c) { return c->desc.dtype == STEM_BF16 ? 2 : 4; }
+
+// Common entry checks; returns STEM_OK to proceed.
+stem_status enter(stem_ctx* c, int64_t T) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  if (T < 0) return fail(c, STEM_ERR_SHAPE, "T = %lld is negative", (long long)T);
+  if (T > c->max_tokens)
+    return fail(c, STEM_ERR_SHAPE, "T = %lld exceeds the context's max_tokens = %lld", (long long)T,
+                (long long)c->max_tokens);
+  hipError_t e = hipSetDevice(c->device);
+  if (e != hipSuccess) return fail(c, STEM_ERR_HIP, "hipSetDevice(%d): %s", c->device, hipGetErrorString(e));
+  if (*reinterpret_cast<volatile int32_t*>(c->flag)) {
+    *reinterpret_cast<volatile int32_t*>(c->flag) = 0;
+    return fail(c, STEM_ERR_ID_RANGE, "an earlier call saw a token id outside [0, E_rows)");
+  }
+  return STEM_OK;
+}
+
+template <typename T>
+hipError_t dmalloc(T** p, size_t n) {
+  *p = nullptr;
+  if (n == 0) n = 1;
+  return hipMalloc(reinterpret_cast<void**>(p), n * sizeof(T));
+}
+
+void release(stem_ctx* c) {
+  if (!c) return;
+  (void)hipSetDevice(c->device);
+  (void)hipDeviceSynchronize();
+  (void)hipFree(c->H_ws); (void)hipFree(c->dG_ws); (void)hipFree(c->dH_ws);
+  for (int i = 0; i < 2; ++i) { (void)hipFree(c->sort_keys[i]); (void)hipFree(c->sort_vals[i]); }
+  (void)hipFree(c->sort_counts); (void)hipFree(c->seg_of); (void)hipFree(c->seg_part);
+  (void)hipFree(c->uniq_dev);
+  if (c->flag) (void)hipHostFree(c->flag);
+  if (c->uniq_pinned) (void)hipHostFree(c->uniq_pinned);
+  if (c->remap_pinned) (void)hipHostFree(c->remap_pinned);
+  if (c->pack_pinned) (void)hipHostFree(c->pack_pinned);
+  free(c->slot);
+  if (c->side) (void)hipStreamDestroy(c->side);
+  if (c->ready) (void)hipEventDestroy(c->ready);
+  for (int i = 0; i < 2; ++i) if (c->pack_done[i]) (void)hipEventDestroy(c->pack_done[i]);
+  if (c->prof_ev) {
+    for (int i = 0; i < 2 * STEM_MAX_PROF_EVENTS; ++i) if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+    free(c->prof_ev);
+  }
+  free(c);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* stem_status_string(stem_status s) {
+  switch (s) {
+    case STEM_OK: return "STEM_OK";
+    case STEM_ERR_INVALID_ARG: return "STEM_ERR_INVALID_ARG";
+    case STEM_ERR_SHAPE: return "STEM_ERR_SHAPE";
+    case STEM_ERR_ID_RANGE: return "STEM_ERR_ID_RANGE";
+    case STEM_ERR_WORKSPACE: return "STEM_ERR_WORKSPACE";
+    case STEM_ERR_UNSUPPORTED: return "STEM_ERR_UNSUPPORTED";
+    case STEM_ERR_HIP: return "STEM_ERR_HIP";
+  }
+  return "STEM_ERR_?";
+}
+
+const char* stem_last_error(const stem_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
+
+stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max_tokens, int device) {
+  if (out) *out = nullptr;
+  if (!out || !desc) return fail(nullptr, STEM_ERR_INVALID_ARG, "stem_create: null argument");
+  if (desc->dtype != STEM_F32 && desc->dtype != STEM_BF16)
+    return fail(nullptr, STEM_ERR_INVALID_ARG, "stem_create: dtype %d is not a stem_dtype", desc->dtype);
+  if (desc->d_model <= 0 || desc->d_ff <= 0 || desc->vocab <= 0 || max_tokens < 0 || max_tokens > (1ll << 30))
+    return fail(nullptr, STEM_ERR_SHAPE, "stem_create: d_model=%d d_ff=%d vocab=%d max_tokens=%lld", desc->d_model,
+                desc->d_ff, desc->vocab, (long long)max_tokens);
+  const int mult = desc->dtype == STEM_BF16 ? 64 : 4;
+  if (desc->d_model % mult || desc->d_ff % mult)
+    return fail(nullptr, STEM_ERR_UNSUPPORTED, "stem_create: d_model=%d and d_ff=%d must be multiples of %d",
+                desc->d_model, desc->d_ff, mult);
+  if ((int64_t)max_tokens * desc->d_ff >= (1ll << 40))
+    return fail(nullptr, STEM_ERR_SHAPE, "stem_create: max_tokens * d_ff too large");
+  HIP_TRY(nullptr, hipSetDevice(device));
+
+  stem_ctx* c = static_cast<stem_ctx*>(calloc(1, sizeof(stem_ctx)));
+  if (!c) return fail(nullptr, STEM_ERR_HIP, "stem_create: out of host memory");
+  c->desc = *desc;
+  c->max_tokens = max_tokens;
+  c->device = device;
+  const size_t es = esize(c);
+  const size_t TF = (size_t)max_tokens * desc->d_ff;
+  hipError_t e = hipSuccess;
+  auto ok = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  ok(hipMalloc(&c->H_ws, std::max<size_t>(TF * es, 16)));
+  ok(hipMalloc(&c->dG_ws, std::max<size_t>(TF * es, 16)));
+  if (desc->dtype == STEM_F32) ok(hipMalloc(&c->dH_ws, std::max<size_t>(TF * 4, 16)));
+  for (int i = 0; i < 2; ++i) {
+    ok(dmalloc(&c->sort_keys[i], (size_t)max_tokens));
+    ok(dmalloc(&c->sort_vals[i], (size_t)max_tokens));
+  }
+  ok(dmalloc(&c->sort_counts, (size_t)stem_sort_count_entries(std::max<int64_t>(max_tokens, 1))));
+  ok(dmalloc(&c->seg_of, (size_t)max_tokens));
+  ok(dmalloc(&c->seg_part, (size_t)stem_seg_chunks(std::max<int64_t>(max_tokens, 1)) * 2 * desc->d_ff));
+  ok(dmalloc(&c->uniq_dev, (size_t)max_tokens));
+  ok(hipHostMalloc(reinterpret_cast<void**>(&c->flag), 64, hipHostMallocDefault));
+  ok(hipHostMalloc(reinterpret_cast<void**>(&c->uniq_pinned), std::max<size_t>(max_tokens, 1) * 4, hipHostMallocDefault));
+  ok(hipHostMalloc(reinterpret_cast<void**>(&c->remap_pinned), std::max<size_t>(max_tokens, 1) * 4, hipHostMallocDefault));
+  ok(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  ok(hipEventCreateWithFlags(&c->ready, hipEventDisableTiming));
+  for (int i = 0; i < 2; ++i) ok(hipEventCreateWithFlags(&c->pack_done[i], hipEventDisableTiming));
+  c->slot = static_cast<int32_t*>(malloc((size_t)desc->vocab * 4));
+  if (e != hipSuccess || !c->slot) {
+    snprintf(g_create_err, sizeof g_create_err, "stem_create: allocation failed: %s",
+             e != hipSuccess ? hipGetErrorString(e) : "host malloc");
+    release(c);
+    return STEM_ERR_HIP;
+  }
+  memset(c->slot, 0xff, (size_t)desc->vocab * 4);
+  *c->flag = 0;
+  c->err[0] = 0;
+  *out = c;
+  return STEM_OK;
+}
+
+void stem_destroy(stem_ctx* ctx) { release(ctx); }
+
+stem_status stem_sync_status(stem_ctx* c, void* stream) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  HIP_TRY(c, hipSetDevice(c->device));
+  HIP_TRY(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  if (*reinterpret_cast<volatile int32_t*>(c->flag)) {
+    *reinterpret_cast<volatile int32_t*>(c->flag) = 0;
+    return fail(c, STEM_ERR_ID_RANGE, "a kernel saw a token id outside [0, E_rows)");
+  }
+  return STEM_OK;
+}
+
+stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, const void* W_gate,
+                             const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y,
+                             void* save_G, void* save_H, void* wait_event, void* stream) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (T == 0) return STEM_OK;
+  if (!x || !ids || !W_gate || !W_down || !E || !y)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_forward: null pointer argument");
+  if (misaligned(x) || misaligned(W_gate) || misaligned(W_down) || misaligned(E) || misaligned(y) ||
+      misaligned(save_G) || misaligned(save_H) || (reinterpret_cast<uintptr_t>(ids) & 3u))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_forward: pointers must be 16-byte aligned");
+  if (E_rows < 1 || E_rows > INT32_MAX) return fail(c, STEM_ERR_SHAPE, "stem_ffn_forward: E_rows = %lld", (long long)E_rows);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int d = c->desc.d_model, F = c->desc.d_ff;
+  void* H = save_H ? save_H : c->H_ws;
+
+  if (c->desc.dtype == STEM_BF16) {
+    GemmArgs a = {};
+    a.A = static_cast<const bf16_t*>(x); a.lda = d;
+    a.B = static_cast<const bf16_t*>(W_gate); a.ldb = d;
+    a.M = (int)T; a.N = F; a.K = d;
+    a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows; a.flag = c->flag;
+    if (!wait_event) {
+      a.outG = static_cast<bf16_t*>(save_G); a.outH = static_cast<bf16_t*>(H);
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE, OP_KC, OP_KC, EPI_GATE, a, s));
+    } else {
+      void* G = save_G ? save_G : c->dG_ws;
+      a.C = G;
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE_PLAIN, OP_KC, OP_KC, EPI_BF16, a, s));
+      HIP_TRY(c, hipStreamWaitEvent(s, static_cast<hipEvent_t>(wait_event), 0));
+      HIP_TRY(c, stem_silu_gather(c, 1, G, ids, E, (int)E_rows, H, T, F, s));
+    }
+    GemmArgs b = {};
+    b.A = static_cast<const bf16_t*>(H); b.lda = F;
+    b.B = static_cast<const bf16_t*>(W_down); b.ldb = F;
+    b.M = (int)T; b.N = d; b.K = F; b.C = y; b.flag = c->flag;
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, EPI_BF16, b, s));
+  } else {
+    float* G = static_cast<float*>(save_G ? save_G : c->dG_ws);
+    HIP_TRY(c, stem_sgemm(c, wait_event ? K_GEMM_GATE_PLAIN : K_GEMM_GATE, static_cast<const float*>(x), d, 1,
+                          static_cast<const float*>(W_gate), d, 1, G, (int)T, F, d, 0, s));
+    if (wait_event) HIP_TRY(c, hipStreamWaitEvent(s, static_cast<hipEvent_t>(wait_event), 0));
+    HIP_TRY(c, stem_silu_gather(c, 0, G, ids, E, (int)E_rows, H, T, F, s));
+    HIP_TRY(c, stem_sgemm(c, K_GEMM_DOWN, static_cast<const float*>(H), F, 1, static_cast<const float*>(W_down), F,
+                          1, static_cast<float*>(y), (int)T, d, F, 0, s));
+  }
+  return STEM_OK;
+}
+
+stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const int32_t* ids,
+                              const void* W_gate, const void* W_down, const void* E, int64_t E_rows,
+                              const void* saved_G, const void* saved_H, int64_t T, void* dx, float* dW_gate,
+                              float* dW_down, void* dU, int accumulate, void* stream) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (!dW_gate || !dW_down) return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_backward: null weight-gradient pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int d = c->desc.d_model, F = c->desc.d_ff;
+  if (T == 0) {
+    if (!accumulate) {
+      HIP_TRY(c, hipMemsetAsync(dW_gate, 0, (size_t)F * d * 4, s));
+      HIP_TRY(c, hipMemsetAsync(dW_down, 0, (size_t)F * d * 4, s));
+    }
+    return STEM_OK;
+  }
+  if (!dy || !x || !ids || !W_gate || !W_down || !E || !saved_G || !dU)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_backward: null pointer argument");
+  if (misaligned(dy) || misaligned(x) || misaligned(W_gate) || misaligned(W_down) || misaligned(E) ||
+      misaligned(saved_G) || misaligned(saved_H) || misaligned(dx) || misaligned(dW_gate) ||
+      misaligned(dW_down) || misaligned(dU) || (reinterpret_cast<uintptr_t>(ids) & 3u))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_backward: pointers must be 16-byte aligned");
+  if (E_rows < 1 || E_rows > INT32_MAX) return fail(c, STEM_ERR_SHAPE, "stem_ffn_backward: E_rows = %lld", (long long)E_rows);
+
+  const void* H = saved_H;
+  if (!H) {
+    HIP_TRY(c, stem_silu_gather(c, c->desc.dtype == STEM_BF16, saved_G, ids, E, (int)E_rows, c->H_ws, T, F, s));
+    H = c->H_ws;
+  }
+  if (c->desc.dtype == STEM_BF16) {
+    const bf16_t* dyb = static_cast<const bf16_t*>(dy);
+    const bf16_t* Hb = static_cast<const bf16_t*>(H);
+    bf16_t* dGb = static_cast<bf16_t*>(c->dG_ws);
+    {  // dH = dy W_down, fused into dU and dG
+      GemmArgs a = {};
+      a.A = dyb; a.lda = d; a.B = static_cast<const bf16_t*>(W_down); a.ldb = F;
+      a.M = (int)T; a.N = F; a.K = d;
+      a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows; a.flag = c->flag;
+      a.inG = static_cast<const bf16_t*>(saved_G); a.outdU = static_cast<bf16_t*>(dU); a.outdG = dGb;
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_MC, EPI_DH, a, s));
+    }
+    {  // dW_down[d,F] = dy^T H
+      GemmArgs a = {};
+      a.A = dyb; a.lda = d; a.B = Hb; a.ldb = F;
+      a.M = d; a.N = F; a.K = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_MC, OP_MC, EPI_F32, a, s));
+    }
+    if (dx) {  // dx = dG W_gate
+      GemmArgs a = {};
+      a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(W_gate); a.ldb = d;
+      a.M = (int)T; a.N = d; a.K = F; a.C = dx; a.flag = c->flag;
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_MC, EPI_BF16, a, s));
+    }
+    {  // dW_gate[F,d] = dG^T x
+      GemmArgs a = {};
+      a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(x); a.ldb = d;
+      a.M = F; a.N = d; a.K = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_MC, EPI_F32, a, s));
+    }
+  } else {
+    const float* dyf = static_cast<const float*>(dy);
+    const float* Hf = static_cast<const float*>(H);
+    const float* Wg = static_cast<const float*>(W_gate);
+    const float* Wd = static_cast<const float*>(W_down);
+    float* dH = static_cast<float*>(c->dH_ws);
+    float* dG = static_cast<float*>(c->dG_ws);
+    HIP_TRY(c, stem_sgemm(c, K_GEMM_DH, dyf, d, 1, Wd, 1, F, dH, (int)T, F, d, 0, s));
+    HIP_TRY(c, stem_dh_epilogue_f32(c, dH, static_cast<const float*>(saved_G), ids, static_cast<const float*>(E),
+                                    (int)E_rows, static_cast<float*>(dU), dG, T, F, s));
+    HIP_TRY(c, stem_sgemm(c, K_GEMM_DWDOWN, dyf, 1, d, Hf, 1, F, dW_down, d, F, (int)T, accumulate, s));
+    if (dx) HIP_TRY(c, stem_sgemm(c, K_GEMM_DX, dG, F, 1, Wg, 1, d, static_cast<float*>(dx), (int)T, d, F, 0, s));
+    HIP_TRY(c, stem_sgemm(c, K_GEMM_DWGATE, dG, 1, F, static_cast<const float*>(x), 1, d, dW_gate, F, d, (int)T,
+                          accumulate, s));
+  }
+  return STEM_OK;
+}
+
+stem_status stem_embed_grad(stem_ctx* c, const int32_t* ids, const void* dU, int64_t T, int32_t* sorted_ids,
+                            int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets, int32_t* n_uniq,
+                            float* dE_rows, void* stream) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (!seg_offsets || !n_uniq) return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: null seg_offsets / n_uniq");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (T == 0) {
+    HIP_TRY(c, hipMemsetAsync(n_uniq, 0, 4, s));
+    HIP_TRY(c, hipMemsetAsync(seg_offsets, 0, 4, s));
+    return STEM_OK;
+  }
+  if (!ids || !sorted_ids || !perm || !uniq_ids)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: null pointer argument");
+  if ((dU == nullptr) != (dE_rows == nullptr))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: dU and dE_rows must both be given or both be NULL");
+  if (misaligned(dU) || misaligned(dE_rows))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: dU and dE_rows must be 16-byte aligned");
+  HIP_TRY(c, stem_sort_unique(c, ids, T, c->desc.vocab, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, s));
+  if (dU)
+    HIP_TRY(c, stem_seg_reduce(c, c->desc.dtype == STEM_BF16, dU, perm, seg_offsets, T, c->desc.d_ff, dE_rows, s));
+  return STEM_OK;
+}
+
+stem_status stem_embed_sparse_adamw(stem_ctx* c, const int32_t* uniq_ids, const int32_t* n_uniq,
+                                    int64_t max_rows, const float* dE_rows, void* E, float* master, float* m,
+                                    float* v, const stem_adamw_hparams* hp, void* stream) {
+  stem_status st = enter(c, 0);
+  if (st != STEM_OK) return st;
+  if (!uniq_ids || !n_uniq || !dE_rows || !E || !m || !v || !hp)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_sparse_adamw: null pointer argument");
+  if (c->desc.dtype == STEM_BF16 && !master)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_sparse_adamw: the bf16 table needs an fp32 master copy");
+  if (misaligned(dE_rows) || misaligned(E) || misaligned(master) || misaligned(m) || misaligned(v))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_sparse_adamw: pointers must be 16-byte aligned");
+  if (max_rows < 0 || max_rows > INT32_MAX) return fail(c, STEM_ERR_SHAPE, "stem_embed_sparse_adamw: max_rows = %lld", (long long)max_rows);
+  if (hp->step < 1) return fail(c, STEM_ERR_SHAPE, "stem_embed_sparse_adamw: step = %lld must be >= 1", (long long)hp->step);
+  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f && hp->beta2 >= 0.f && hp->beta2 < 1.f))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_sparse_adamw: betas must lie in [0, 1)");
+  HIP_TRY(c, stem_adamw(c, c->desc.dtype == STEM_BF16, uniq_ids, n_uniq, max_rows, dE_rows, E, master, m, v,
+                        c->desc.d_ff, *hp, static_cast<hipStream_t>(stream)));
+  return STEM_OK;
+}
+
+stem_status stem_prefetch_rows(stem_ctx* c, const void* E_host, const int32_t* ids_host, int64_t T,
+                               void* E_compact, int64_t cap, int32_t* remap, int64_t* n_uniq_host,
+                               int32_t* uniq_ids_host, void** ready_event) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (!E_host || (!ids_host && T > 0) || !E_compact || (!remap && T > 0) || !n_uniq_host || !ready_event)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_prefetch_rows: null pointer argument");
+  if (misaligned(E_host) || misaligned(E_compact))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_prefetch_rows: tables must be 16-byte aligned");
+  if (cap < 0) return fail(c, STEM_ERR_SHAPE, "stem_prefetch_rows: cap = %lld", (long long)cap);
+  const int V = c->desc.vocab;
+  const size_t row_bytes = (size_t)c->desc.d_ff * esize(c);
+
+  // The pinned staging arrays are reused: wait until the previous prefetch's copies are done.
+  HIP_TRY(c, hipStreamSynchronize(c->side));
+
+  // De-duplicate: mark, then walk the marked ids in ascending order.
+  for (int64_t i = 0; i < T; ++i) {
+    const int32_t t = ids_host[i];
+    if ((uint32_t)t >= (uint32_t)V) {
+      for (int64_t k = 0; k < i; ++k) c->slot[ids_host[k]] = -1;
+      return fail(c, STEM_ERR_ID_RANGE, "stem_prefetch_rows: ids[%lld] = %d is outside [0, %d)", (long long)i, t, V);
+    }
+    c->slot[t] = 0;
+  }
+  int64_t U = 0;
+  if (T > 0) {
+    // scanning all V slots costs O(V); sorting the marked ids costs O(U log U).  Take the cheaper.
+    if ((int64_t)V <= 16 * T) {
+      for (int32_t t = 0; t < V; ++t)
+        if (c->slot[t] == 0) { c->slot[t] = (int32_t)U; c->uniq_pinned[U++] = t; }
+    } else {
+      for (int64_t i = 0; i < T; ++i) {
+        const int32_t t = ids_host[i];
+        if (c->slot[t] == 0) { c->slot[t] = 1; c->uniq_pinned[U++] = t; }
+      }
+      std::sort(c->uniq_pinned, c->uniq_pinned + U);
+      for (int64_t j = 0; j < U; ++j) c->slot[c->uniq_pinned[j]] = (int32_t)j;
+    }
+  }
+  for (int64_t i = 0; i < T; ++i) c->remap_pinned[i] = c->slot[ids_host[i]];
+  for (int64_t j = 0; j < U; ++j) c->slot[c->uniq_pinned[j]] = -1;
+  *n_uniq_host = U;
+  if (uniq_ids_host) memcpy(uniq_ids_host, c->uniq_pinned, (size_t)std::min<int64_t>(U, cap) * 4);
+  if (U > cap)
+    return fail(c, STEM_ERR_WORKSPACE, "stem_prefetch_rows: %lld distinct ids but E_compact holds %lld rows",
+                (long long)U, (long long)cap);
+
+  if (T > 0) HIP_TRY(c, hipMemcpyAsync(remap, c->remap_pinned, (size_t)T * 4, hipMemcpyHostToDevice, c->side));
+  const char* mode = getenv("STEM_PREFETCH_MODE");
+  if (mode && strcmp(mode, "memcpy") == 0) {
+    // Pack the rows into pinned staging with a few host threads and copy chunk by chunk,
+    // packing chunk i+1 while chunk i is on the link.
+    if (!c->pack_pinned) {
+      c->pack_bytes = std::max<size_t>((size_t)64 << 20, 2 * row_bytes);
+      HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pack_pinned), c->pack_bytes, hipHostMallocDefault));
+    }
+    const size_t half = c->pack_bytes / 2;
+    const int64_t rows_per = (int64_t)(half / row_bytes);
+    const unsigned hw = std::thread::hardware_concurrency();
+    const int nthr = (int)std::max(1u, std::min(8u, hw ? hw : 1u));
+    int chunk = 0;
+    for (int64_t j0 = 0; j0 < U; j0 += rows_per, ++chunk) {
+      const int64_t nrows = std::min(rows_per, U - j0);
+      char* stage = c->pack_pinned + (size_t)(chunk & 1) * half;
+      if (chunk >= 2) HIP_TRY(c, hipEventSynchronize(c->pack_done[chunk & 1]));
+      std::vector<std::thread> pool;
+      for (int t = 0; t < nthr; ++t)
+        pool.emplace_back([=]() {
+          for (int64_t r = t; r < nrows; r += nthr)
+            memcpy(stage + (size_t)r * row_bytes,
+                   static_cast<const char*>(E_host) + (size_t)c->uniq_pinned[j0 + r] * row_bytes, row_bytes);
+        });
+      for (auto& th : pool) th.join();
+      HIP_TRY(c, hipMemcpyAsync(static_cast<char*>(E_compact) + (size_t)j0 * row_bytes, stage,
+                                (size_t)nrows * row_bytes, hipMemcpyHostToDevice, c->side));
+      HIP_TRY(c, hipEventRecord(c->pack_done[chunk & 1], c->side));
+    }
+  } else if (U > 0) {
+    HIP_TRY(c, hipMemcpyAsync(c->uniq_dev, c->uniq_pinned, (size_t)U * 4, hipMemcpyHostToDevice, c->side));
+    HIP_TRY(c, stem_copy_rows_kernel(c, E_host, c->uniq_dev, U, (int64_t)row_bytes, E_compact, c->side));
+  }
+  HIP_TRY(c, hipEventRecord(c->ready, c->side));
+  *ready_event = c->ready;
+  return STEM_OK;
+}
+
+stem_status stem_profile_enable(stem_ctx* c, int on) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  if (on && !c->prof_ev) {
+    HIP_TRY(c, hipSetDevice(c->device));
+    c->prof_ev = static_cast<hipEvent_t*>(calloc(2 * STEM_MAX_PROF_EVENTS, sizeof(hipEvent_t)));
+    if (!c->prof_ev) return fail(c, STEM_ERR_HIP, "stem_profile_enable: out of host memory");
+    for (int i = 0; i < 2 * STEM_MAX_PROF_EVENTS; ++i) HIP_TRY(c, hipEventCreate(&c->prof_ev[i]));
+  }
+  c->prof_on = on ? 1 : 0;
+  return STEM_OK;
+}
+
+int stem_profile_kernels(void) { return K_COUNT_; }
+
+static stem_status prof_collect(stem_ctx* c) {
+  if (c->prof_n == 0) return STEM_OK;
+  HIP_TRY(c, hipSetDevice(c->device));
+  HIP_TRY(c, hipDeviceSynchronize());
+  for (int i = 0; i < c->prof_n; ++i) {
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+    c->prof_ms[c->prof_kid[i]] += ms;
+    c->prof_launches[c->prof_kid[i]] += 1;
+  }
+  c->prof_n = 0;
+  return STEM_OK;
+}
+
+stem_status stem_profile_read(stem_ctx* c, int k, const char** name, double* total_ms, int64_t* launches) {
+  if (!c || k < 0 || k >= K_COUNT_) return STEM_ERR_INVALID_ARG;
+  stem_status st = prof_collect(c);
+  if (st != STEM_OK) return st;
+  if (name) *name = kKernelNames[k];
+  if (total_ms) *total_ms = c->prof_ms[k];
+  if (launches) *launches = c->prof_launches[k];
+  return STEM_OK;
+}
+
+stem_status stem_profile_reset(stem_ctx* c) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  stem_status st = prof_collect(c);
+  for (int k = 0; k < K_COUNT_; ++k) { c->prof_ms[k] = 0; c->prof_launches[k] = 0; }
+  return st;
+}
+
+}  // extern "C"

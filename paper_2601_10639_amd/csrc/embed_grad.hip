@@ -1,0 +1,393 @@
+// Gradient of the per-layer table, restricted to the rows a batch touches:
+// stable LSD radix sort of (token id, position), distinct ids with run offsets, and a
+// fixed-order segmented sum of the per-token row gradients.  Integer results are unique,
+// floating sums use one fixed association, so every run gives the same bits.
+#include "stem_internal.h"
+
+namespace {
+
+constexpr int RADIX_BITS = 6;          // one digit value per lane of a wavefront
+constexpr int RADIX = 1 << RADIX_BITS;
+constexpr int SORT_WAVES = 16;         // wavefronts per workgroup
+constexpr int KEYS_PER_WAVE = 256;     // 4 rounds of 64
+constexpr int SORT_TILE = SORT_WAVES * KEYS_PER_WAVE;
+
+__device__ __forceinline__ int load_key(const int32_t* __restrict__ keys, int64_t i, int V, int first_pass,
+                                        int32_t* flag) {
+  int k = keys[i];
+  if (first_pass && (unsigned)k >= (unsigned)V) {
+    *flag = 1;
+    k = k < 0 ? 0 : V - 1;
+  }
+  return k;
+}
+
+// counts[d * nW + gw] = number of keys with digit d among wavefront gw's 256 keys
+__global__ __launch_bounds__(1024) void sort_count_kernel(const int32_t* __restrict__ keys, int64_t T, int V,
+                                                          int shift, int first_pass, int nW,
+                                                          int32_t* __restrict__ counts, int32_t* flag) {
+  __shared__ int hist[SORT_WAVES][RADIX];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int gw = blockIdx.x * SORT_WAVES + wave;
+  hist[wave][lane] = 0;
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int r = 0; r < KEYS_PER_WAVE / 64; ++r) {
+    const int64_t i = (int64_t)gw * KEYS_PER_WAVE + r * 64 + lane;
+    if (i < T) {
+      const int d = (load_key(keys, i, V, first_pass, flag) >> shift) & (RADIX - 1);
+      atomicAdd(&hist[wave][d], 1);
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (gw < nW) counts[lane * nW + gw] = hist[wave][lane];
+}
+
+// in-place exclusive scan of n ints by one workgroup of 1024 threads
+__global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ a, int n) {
+  __shared__ int wsum[16];
+  __shared__ int carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (n + 1023) / 1024;
+  const int b = tid * per, e = min(n, b + per);
+  int s = 0;
+  for (int i = b; i < e; ++i) s += a[i];
+  int inc = s;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  if (tid == 0) {
+    int c = 0;
+    for (int w = 0; w < 16; ++w) { const int t = wsum[w]; wsum[w] = c; c += t; }
+    carry_s = c;
+  }
+  __syncthreads();
+  int run = wsum[wave] + inc - s;
+  for (int i = b; i < e; ++i) { const int t = a[i]; a[i] = run; run += t; }
+}
+
+// Stable scatter by digit.  Within a wavefront, a key's rank among equal digits of the
+// same 64-key round comes from ballots; rounds and wavefronts are ordered by the scan.
+__global__ __launch_bounds__(1024) void sort_scatter_kernel(const int32_t* __restrict__ keys,
+                                                            const int32_t* __restrict__ vals, int64_t T, int V,
+                                                            int shift, int first_pass, int nW,
+                                                            const int32_t* __restrict__ counts,
+                                                            int32_t* __restrict__ out_keys,
+                                                            int32_t* __restrict__ out_vals, int32_t* flag) {
+  __shared__ int base[SORT_WAVES][RADIX];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int gw = blockIdx.x * SORT_WAVES + wave;
+  if (gw >= nW) return;
+  base[wave][lane] = counts[lane * nW + gw];
+  __builtin_amdgcn_wave_barrier();
+  const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll 1
+  for (int r = 0; r < KEYS_PER_WAVE / 64; ++r) {
+    const int64_t i = (int64_t)gw * KEYS_PER_WAVE + r * 64 + lane;
+    const bool valid = i < T;
+    int key = 0, val = 0, d = 0;
+    if (valid) {
+      key = load_key(keys, i, V, first_pass, flag);
+      val = first_pass ? (int)i : vals[i];
+      d = (key >> shift) & (RADIX - 1);
+    }
+    uint64_t same = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < RADIX_BITS; ++b) {
+      const bool bit = (d >> b) & 1;
+      const uint64_t bb = __ballot(valid && bit);
+      same &= bit ? bb : ~bb;
+    }
+    int pos = 0;
+    if (valid) {
+      const int rank = __popcll(same & below);
+      pos = base[wave][d] + rank;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (valid && (same & below) == 0) base[wave][d] += __popcll(same);
+    __builtin_amdgcn_wave_barrier();
+    if (valid) {
+      out_keys[pos] = key;
+      out_vals[pos] = val;
+    }
+  }
+}
+
+// Distinct ids, run offsets, and for every sorted position the index of its run.
+constexpr int UNIQ_ITEMS = 8;
+__global__ __launch_bounds__(1024) void unique_kernel(const int32_t* __restrict__ sorted, int64_t T,
+                                                      int32_t* __restrict__ uniq_ids,
+                                                      int32_t* __restrict__ seg_offsets,
+                                                      int32_t* __restrict__ n_uniq, int32_t* __restrict__ seg_of) {
+  __shared__ int wsum[16];
+  __shared__ int total_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int carry = 0;  // runs started before this sweep
+  for (int64_t sweep = 0; sweep < T; sweep += 1024 * UNIQ_ITEMS) {
+    const int64_t b = sweep + (int64_t)tid * UNIQ_ITEMS;
+    int key[UNIQ_ITEMS];
+    int prev = (b > 0 && b <= T) ? sorted[b - 1] : -1;
+    int heads = 0;
+    unsigned headmask = 0;
+#pragma unroll
+    for (int u = 0; u < UNIQ_ITEMS; ++u) {
+      const int64_t k = b + u;
+      if (k < T) {
+        key[u] = sorted[k];
+        const bool h = (k == 0) || key[u] != prev;
+        prev = key[u];
+        if (h) { ++heads; headmask |= 1u << u; }
+      }
+    }
+    int inc = heads;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    if (tid == 0) {
+      int c = 0;
+      for (int w = 0; w < 16; ++w) { const int t = wsum[w]; wsum[w] = c; c += t; }
+      total_s = c;
+    }
+    __syncthreads();
+    int run = carry + wsum[wave] + inc - heads;  // runs started before this thread's first item
+#pragma unroll
+    for (int u = 0; u < UNIQ_ITEMS; ++u) {
+      const int64_t k = b + u;
+      if (k < T) {
+        if (headmask & (1u << u)) {
+          uniq_ids[run] = key[u];
+          seg_offsets[run] = (int)k;
+          ++run;
+        }
+        seg_of[k] = run - 1;
+      }
+    }
+    carry += total_s;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    seg_offsets[carry] = (int)T;
+    *n_uniq = carry;
+  }
+}
+
+// ---- segmented sum -----------------------------------------------------------------
+constexpr int SEG_ROWS = 32;  // sorted positions per chunk
+
+template <bool BF16> struct RowVec;
+template <> struct RowVec<true> {
+  static constexpr int COLS = 8;
+  static __device__ __forceinline__ void load(const void* base, int64_t row, int F, int col, float (&f)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(base) + row * F + col);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f[2 * q] = __uint_as_float(w[q] << 16);
+      f[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+    }
+  }
+};
+template <> struct RowVec<false> {
+  static constexpr int COLS = 4;
+  static __device__ __forceinline__ void load(const void* base, int64_t row, int F, int col, float (&f)[4]) {
+    const float4 v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + row * F + col);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
+};
+
+template <int COLS>
+__device__ __forceinline__ void store_cols(float* dst, const float (&a)[COLS]) {
+#pragma unroll
+  for (int q = 0; q < COLS; q += 4) *reinterpret_cast<float4*>(dst + q) = make_float4(a[q], a[q + 1], a[q + 2], a[q + 3]);
+}
+
+// One workgroup sums the rows of sorted positions [c*SEG_ROWS, (c+1)*SEG_ROWS) for a slab
+// of 256*COLS columns, in ascending position.  A run that lies wholly inside the chunk
+// is written to its output row; the (at most two) pieces of runs that cross the chunk's
+// borders go to part[c][0] (piece holding the chunk's first position) or part[c][1].
+template <bool BF16>
+__global__ __launch_bounds__(256) void seg_reduce_kernel(const void* __restrict__ dU,
+                                                         const int32_t* __restrict__ perm,
+                                                         const int32_t* __restrict__ seg_of,
+                                                         const int32_t* __restrict__ seg_offsets, int64_t T,
+                                                         int F, float* __restrict__ dE_rows,
+                                                         float* __restrict__ part) {
+  constexpr int COLS = RowVec<BF16>::COLS;
+  const int c = blockIdx.x;
+  const int k0 = c * SEG_ROWS;
+  const int k1 = (int)min((int64_t)k0 + SEG_ROWS, T);
+  const int col = (blockIdx.y * 256 + threadIdx.x) * COLS;
+  if (col >= F) return;
+  const int first_seg = seg_of[k0];
+  float acc[COLS];
+#pragma unroll
+  for (int q = 0; q < COLS; ++q) acc[q] = 0.f;
+  int cur = first_seg;
+
+  auto flush = [&](int j) {
+    const int lo = seg_offsets[j], hi = seg_offsets[j + 1];
+    float* dst;
+    if (lo >= k0 && hi <= k1) dst = dE_rows + (int64_t)j * F + col;
+    else dst = part + ((int64_t)c * 2 + (j == first_seg ? 0 : 1)) * F + col;
+    store_cols<COLS>(dst, acc);
+  };
+
+  constexpr int UNR = 8;
+  for (int kb = k0; kb < k1; kb += UNR) {
+    float data[UNR][COLS];
+    int segs[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int k = kb + u;
+      if (k < k1) {
+        segs[u] = seg_of[k];
+        RowVec<BF16>::load(dU, perm[k], F, col, data[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int k = kb + u;
+      if (k < k1) {
+        if (segs[u] != cur) {
+          flush(cur);
+          cur = segs[u];
+#pragma unroll
+          for (int q = 0; q < COLS; ++q) acc[q] = 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < COLS; ++q) acc[q] += data[u][q];
+      }
+    }
+  }
+  flush(cur);
+}
+
+// The chunk in which a border-crossing run starts adds up that run's pieces in chunk order.
+template <int COLS>
+__global__ __launch_bounds__(256) void seg_combine_kernel(const int32_t* __restrict__ seg_of,
+                                                          const int32_t* __restrict__ seg_offsets, int64_t T,
+                                                          int F, float* __restrict__ dE_rows,
+                                                          const float* __restrict__ part) {
+  const int c = blockIdx.x;
+  const int k0 = c * SEG_ROWS;
+  const int k1 = (int)min((int64_t)k0 + SEG_ROWS, T);
+  const int j = seg_of[k1 - 1];
+  const int lo = seg_offsets[j], hi = seg_offsets[j + 1];
+  if (!(lo >= k0 && hi > k1)) return;
+  const int col = (blockIdx.y * 256 + threadIdx.x) * COLS;
+  if (col >= F) return;
+  const int slot = (seg_of[k0] == j) ? 0 : 1;
+  const int ce = (hi - 1) / SEG_ROWS;
+  float acc[COLS];
+  {
+    const float* src = part + ((int64_t)c * 2 + slot) * F + col;
+#pragma unroll
+    for (int q = 0; q < COLS; ++q) acc[q] = src[q];
+  }
+  constexpr int UNR = 8;
+  for (int cb = c + 1; cb <= ce; cb += UNR) {
+    float data[UNR][COLS];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      if (cb + u <= ce) {
+        const float* src = part + ((int64_t)(cb + u) * 2) * F + col;
+#pragma unroll
+        for (int q = 0; q < COLS; q += 4) {
+          const float4 v = *reinterpret_cast<const float4*>(src + q);
+          data[u][q] = v.x; data[u][q + 1] = v.y; data[u][q + 2] = v.z; data[u][q + 3] = v.w;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (cb + u <= ce)
+#pragma unroll
+        for (int q = 0; q < COLS; ++q) acc[q] += data[u][q];
+  }
+  store_cols<COLS>(dE_rows + (int64_t)j * F + col, acc);
+}
+
+int bits_for(int V) {
+  int b = 1;
+  while (b < 31 && (1ll << b) < (long long)V) ++b;
+  return b;
+}
+
+}  // namespace
+
+int64_t stem_seg_chunks(int64_t max_tokens) { return (max_tokens + SEG_ROWS - 1) / SEG_ROWS; }
+int64_t stem_sort_count_entries(int64_t max_tokens) {
+  const int64_t tiles = (max_tokens + SORT_TILE - 1) / SORT_TILE;
+  return tiles * SORT_WAVES * RADIX;
+}
+
+hipError_t stem_sort_unique(stem_ctx* ctx, const int32_t* ids, int64_t T, int V, int32_t* sorted_ids,
+                            int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets, int32_t* n_uniq,
+                            hipStream_t s) {
+  const int tiles = (int)((T + SORT_TILE - 1) / SORT_TILE);
+  const int nW = tiles * SORT_WAVES;
+  const int passes = (bits_for(V) + RADIX_BITS - 1) / RADIX_BITS;
+  const int32_t* src_k = ids;
+  const int32_t* src_v = nullptr;
+  for (int p = 0; p < passes; ++p) {
+    int32_t* dst_k = (p == passes - 1) ? sorted_ids : ctx->sort_keys[p & 1];
+    int32_t* dst_v = (p == passes - 1) ? perm : ctx->sort_vals[p & 1];
+    const int shift = p * RADIX_BITS;
+    {
+      ProfScope ps(ctx, K_SORT_COUNT, s);
+      hipLaunchKernelGGL(sort_count_kernel, dim3(tiles), dim3(1024), 0, s, src_k, T, V, shift, p == 0, nW,
+                         ctx->sort_counts, ctx->flag);
+    }
+    {
+      ProfScope ps(ctx, K_SORT_SCAN, s);
+      hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, s, ctx->sort_counts, nW * RADIX);
+    }
+    {
+      ProfScope ps(ctx, K_SORT_SCATTER, s);
+      hipLaunchKernelGGL(sort_scatter_kernel, dim3(tiles), dim3(1024), 0, s, src_k, src_v, T, V, shift, p == 0,
+                         nW, ctx->sort_counts, dst_k, dst_v, ctx->flag);
+    }
+    src_k = dst_k;
+    src_v = dst_v;
+  }
+  {
+    ProfScope ps(ctx, K_UNIQUE, s);
+    hipLaunchKernelGGL(unique_kernel, dim3(1), dim3(1024), 0, s, sorted_ids, T, uniq_ids, seg_offsets, n_uniq,
+                       ctx->seg_of);
+  }
+  return hipGetLastError();
+}
+
+hipError_t stem_seg_reduce(stem_ctx* ctx, int is_bf16, const void* dU, const int32_t* perm,
+                           const int32_t* seg_offsets, int64_t T, int F, float* dE_rows, hipStream_t s) {
+  const int chunks = (int)((T + SEG_ROWS - 1) / SEG_ROWS);
+  const int cols = is_bf16 ? 8 : 4;
+  const int slabs = (F + 256 * cols - 1) / (256 * cols);
+  {
+    ProfScope ps(ctx, K_SEG_REDUCE, s);
+    if (is_bf16)
+      hipLaunchKernelGGL(seg_reduce_kernel<true>, dim3(chunks, slabs), dim3(256), 0, s, dU, perm, ctx->seg_of,
+                         seg_offsets, T, F, dE_rows, ctx->seg_part);
+    else
+      hipLaunchKernelGGL(seg_reduce_kernel<false>, dim3(chunks, slabs), dim3(256), 0, s, dU, perm, ctx->seg_of,
+                         seg_offsets, T, F, dE_rows, ctx->seg_part);
+  }
+  {
+    ProfScope ps(ctx, K_SEG_COMBINE, s);
+    if (is_bf16)
+      hipLaunchKernelGGL(seg_combine_kernel<8>, dim3(chunks, slabs), dim3(256), 0, s, ctx->seg_of, seg_offsets, T,
+                         F, dE_rows, ctx->seg_part);
+    else
+      hipLaunchKernelGGL(seg_combine_kernel<4>, dim3(chunks, slabs), dim3(256), 0, s, ctx->seg_of, seg_offsets, T,
+                         F, dE_rows, ctx->seg_part);
+  }
+  return hipGetLastError();
+}

@@ -1,0 +1,148 @@
+// Internal declarations shared by libstem's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/stem.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+// ---- kernel ids for the profiling table -----------------------------------------
+enum StemKernelId {
+  K_GEMM_GATE = 0,   // G = X Wg^T with fused SiLU*gather epilogue
+  K_GEMM_GATE_PLAIN, // G = X Wg^T, plain store (host-resident table mode)
+  K_GEMM_DOWN,       // Y = H Wd^T
+  K_GEMM_DH,         // dH = dY Wd with fused dU/dG epilogue
+  K_GEMM_DX,         // dX = dG Wg
+  K_GEMM_DWDOWN,     // dWd = dY^T H
+  K_GEMM_DWGATE,     // dWg = dG^T X
+  K_SILU_GATHER,     // H = SiLU(G) * E[ids] (stand-alone)
+  K_DH_EPILOGUE,     // fp32 path: dU, dG from dH
+  K_SORT_COUNT,
+  K_SORT_SCAN,
+  K_SORT_SCATTER,
+  K_SORT_FUSED,
+  K_UNIQUE,
+  K_SEG_REDUCE,
+  K_SEG_COMBINE,
+  K_ADAMW,
+  K_ROW_COPY,        // host-resident rows -> compact device table
+  K_COUNT_
+};
+
+#define STEM_MAX_PROF_EVENTS 8192
+
+struct stem_ctx {
+  stem_layer_desc desc;
+  int64_t max_tokens;
+  int device;
+  char err[512];
+
+  // scratch, all device memory unless noted
+  void* H_ws;            // [max_tokens, F] context dtype
+  void* dG_ws;           // [max_tokens, F] context dtype
+  void* dH_ws;           // [max_tokens, F] fp32, STEM_F32 only
+  int32_t* sort_keys[2]; // [max_tokens]
+  int32_t* sort_vals[2]; // [max_tokens]
+  int32_t* sort_counts;  // [64 * waves]
+  int32_t* seg_of;       // [max_tokens] index of the segment each sorted position is in
+  float* seg_part;       // [chunks][2][F] partial sums of segments that cross chunk borders
+  int32_t* flag;         // pinned host int, device-visible: sticky id-range flag
+
+  // host-resident table mode
+  hipStream_t side;
+  hipEvent_t ready;
+  int32_t* slot;         // host [V], -1 = absent
+  int32_t* uniq_pinned;  // pinned host [max_tokens]
+  int32_t* remap_pinned; // pinned host [max_tokens]
+  int32_t* uniq_dev;     // device [max_tokens]
+  char* pack_pinned;     // pinned host staging for the memcpy mode
+  size_t pack_bytes;
+  hipEvent_t pack_done[2];
+
+  // profiling
+  int prof_on;
+  hipEvent_t* prof_ev;   // 2 * STEM_MAX_PROF_EVENTS
+  int prof_kid[STEM_MAX_PROF_EVENTS];
+  int prof_n;
+  double prof_ms[K_COUNT_];
+  int64_t prof_launches[K_COUNT_];
+};
+
+// Brackets a launch with events when profiling is on.
+struct ProfScope {
+  stem_ctx* c;
+  hipStream_t s;
+  int idx;
+  ProfScope(stem_ctx* ctx, int kid, hipStream_t st) : c(ctx), s(st), idx(-1) {
+    if (c && c->prof_on && c->prof_n < STEM_MAX_PROF_EVENTS) {
+      idx = c->prof_n++;
+      c->prof_kid[idx] = kid;
+      (void)hipEventRecord(c->prof_ev[2 * idx], s);
+    }
+  }
+  ~ProfScope() {
+    if (idx >= 0) (void)hipEventRecord(c->prof_ev[2 * idx + 1], s);
+  }
+};
+
+// ---- bf16 MFMA GEMM family (gemm_bf16.hip) ---------------------------------------
+// C[m,n] = sum_k Aop[m,k] * Bop[n,k].  An operand is "KC" when stored [rows, K] with K
+// contiguous, "MC" when stored [K, rows] with rows contiguous.
+enum { OP_KC = 0, OP_MC = 1 };
+enum GemmEpilogue {
+  EPI_BF16 = 0, // C -> bf16 [M,N]
+  EPI_F32,      // C -> fp32 [M,N], optional +=
+  EPI_GATE,     // G (optional) and H = SiLU(C) * E[ids[m], n], both bf16
+  EPI_DH        // dU = C * SiLU(G), dG = C * E[ids[m], n] * SiLU'(G), both bf16
+};
+
+struct GemmArgs {
+  const bf16_t* A; // M-side operand
+  const bf16_t* B; // N-side operand
+  int M, N, K;
+  int lda, ldb;    // leading dimensions of the stored operands
+  void* C;         // EPI_BF16 / EPI_F32 output, ld = N
+  int accumulate;  // EPI_F32: add to C
+  const int32_t* ids;
+  const bf16_t* E;
+  int E_rows;
+  bf16_t* outG;    // EPI_GATE: may be null
+  bf16_t* outH;    // EPI_GATE
+  const bf16_t* inG; // EPI_DH
+  bf16_t* outdU;   // EPI_DH
+  bf16_t* outdG;   // EPI_DH
+  int32_t* flag;
+};
+
+hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const GemmArgs& a, hipStream_t s);
+
+// ---- fp32 path and element-wise kernels (kernels_f32.hip) -------------------------
+// C[m,n] (+)= sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]
+hipError_t stem_sgemm(stem_ctx* ctx, int kid, const float* A, int64_t sam, int64_t sak, const float* B,
+                      int64_t sbn, int64_t sbk, float* C, int M, int N, int K, int accumulate, hipStream_t s);
+// H = SiLU(G) * E[ids]; is_bf16 selects the element type of G, E, H
+hipError_t stem_silu_gather(stem_ctx* ctx, int is_bf16, const void* G, const int32_t* ids, const void* E,
+                            int E_rows, void* H, int64_t T, int F, hipStream_t s);
+// fp32: dU = dH * SiLU(G); dG = dH * E[ids] * SiLU'(G)
+hipError_t stem_dh_epilogue_f32(stem_ctx* ctx, const float* dH, const float* G, const int32_t* ids,
+                                const float* E, int E_rows, float* dU, float* dG, int64_t T, int F,
+                                hipStream_t s);
+
+// ---- table gradient (embed_grad.hip) ----------------------------------------------
+hipError_t stem_sort_unique(stem_ctx* ctx, const int32_t* ids, int64_t T, int V, int32_t* sorted_ids,
+                            int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets, int32_t* n_uniq,
+                            hipStream_t s);
+hipError_t stem_seg_reduce(stem_ctx* ctx, int is_bf16, const void* dU, const int32_t* perm,
+                           const int32_t* seg_offsets, int64_t T, int F, float* dE_rows, hipStream_t s);
+int64_t stem_seg_chunks(int64_t max_tokens);
+int64_t stem_sort_count_entries(int64_t max_tokens);
+
+// ---- optimiser (adamw.hip) ----------------------------------------------------------
+hipError_t stem_adamw(stem_ctx* ctx, int is_bf16, const int32_t* uniq_ids, const int32_t* n_uniq,
+                      int64_t max_rows, const float* g, void* E, float* master, float* m, float* v, int F,
+                      const stem_adamw_hparams& hp, hipStream_t s);
+
+// ---- host-resident rows (prefetch.hip) ----------------------------------------------
+hipError_t stem_copy_rows_kernel(stem_ctx* ctx, const void* E_host, const int32_t* uniq_dev, int64_t n,
+                                 int64_t row_bytes, void* E_compact, hipStream_t s);

@@ -1,0 +1,83 @@
+"""CPU-only checks of the boundary: the shared library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_10639_amd import stemlib as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(L.LIB_PATH):
+        from paper_2601_10639_amd import build
+        build.build()
+    return L.lib()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "stem.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(stem_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    declared = _declared_symbols()
+    assert len(declared) >= 10
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in stem.h but not exported by libstem.so"
+    assert sorted(L.SYMBOLS) == declared
+    for name in ("stem_create", "stem_destroy", "stem_ffn_forward", "stem_ffn_backward", "stem_embed_grad",
+                 "stem_embed_sparse_adamw", "stem_prefetch_rows", "stem_sync_status"):
+        assert callable(getattr(L, name))
+
+
+def test_status_strings(lib):
+    names = [L.status_string(i) for i in range(7)]
+    assert names == ["STEM_OK", "STEM_ERR_INVALID_ARG", "STEM_ERR_SHAPE", "STEM_ERR_ID_RANGE",
+                     "STEM_ERR_WORKSPACE", "STEM_ERR_UNSUPPORTED", "STEM_ERR_HIP"]
+    assert lib.stem_profile_kernels() >= 10
+
+
+def test_create_rejects_bad_descriptors_on_the_host(lib):
+    out = ctypes.c_void_p(123)
+
+    def create(d, F, V, dt, T):
+        desc = L.stem_layer_desc(d, F, V, dt)
+        return lib.stem_create(ctypes.byref(out), ctypes.byref(desc), T, 0)
+
+    assert create(100, 256, 10, L.STEM_BF16, 8) == L.STEM_ERR_UNSUPPORTED   # d_model not a multiple of 64
+    assert out.value is None
+    assert b"multiples of 64" in lib.stem_last_error(None)
+    assert create(64, 64, 10, 7, 8) == L.STEM_ERR_INVALID_ARG               # unknown dtype
+    assert create(64, 64, 0, L.STEM_BF16, 8) == L.STEM_ERR_SHAPE            # empty vocabulary
+    assert create(64, 64, 10, L.STEM_BF16, -1) == L.STEM_ERR_SHAPE          # negative capacity
+    assert create(6, 8, 10, L.STEM_F32, 8) == L.STEM_ERR_UNSUPPORTED        # fp32 needs multiples of 4
+    assert lib.stem_create(None, None, 8, 0) == L.STEM_ERR_INVALID_ARG
+
+
+def test_null_context_is_refused(lib):
+    z = ctypes.c_void_p(None)
+    assert lib.stem_ffn_forward(z, z, z, z, z, z, 1, 1, z, z, z, z, z) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_ffn_backward(z, z, z, z, z, z, z, 1, z, z, 1, z, z, z, z, 0, z) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_embed_grad(z, z, z, 1, z, z, z, z, z, z, z) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_embed_sparse_adamw(z, z, z, 1, z, z, z, z, z, None, z) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_sync_status(z, z) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_profile_enable(z, 1) == L.STEM_ERR_INVALID_ARG
+    lib.stem_destroy(z)  # allowed
+
+
+def test_binding_refuses_wrong_dtypes_before_calling():
+    import torch
+
+    class Fake:
+        handle = ctypes.c_void_p(None)
+        torch_dtype = torch.bfloat16
+
+    x = torch.zeros(4, 64, dtype=torch.float32)
+    with pytest.raises(TypeError):
+        L.stem_ffn_forward(Fake(), x, torch.zeros(4, dtype=torch.int32), x, x, x, x)

@@ -1,0 +1,250 @@
+"""GPU parity: libstem (through the C ABI) against the CPU oracle on the same seeded inputs.
+Integer outputs are compared bit for bit; floating outputs by max |gpu-ref| / max |ref|."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stem_oracle as O
+from paper_2601_10639_amd import inputs, stemlib as L
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _oracle_all(inp):
+    f64 = {k: inputs.to_f64(v) for k, v in inp.items() if k != "ids"}
+    ids = inp["ids"].cpu().numpy()
+    y, fw = O.ffn_forward(f64["x"], ids, f64["W_gate"], f64["W_down"], f64["E"])
+    bw = O.ffn_backward(f64["dy"], f64["x"], ids, f64["W_gate"], f64["W_down"], f64["E"])
+    eg = O.embed_grad(ids, bw["dU"])
+    return y, fw, bw, eg
+
+
+def _pipeline_case(shape, T, seed, save_H=True, ids=None):
+    inp = inputs.layer_inputs(shape, seed, device=DEV, tokens=T, ids=ids)
+    ctx = Hn.make_ctx(shape, max(T, 1))
+    tol = Hn.TOL[shape.dtype]
+    out = Hn.hip_forward_backward(ctx, inp, save_H=save_H)
+    eg = Hn.hip_embed_grad(ctx, inp["ids"], out["dU"], shape.vocab)
+    L.stem_sync_status(ctx)
+    y, fw, bw, oeg = _oracle_all(inp)
+    errs = {
+        "y": Hn.max_rel(out["y"].float().cpu(), y),
+        "G": Hn.max_rel(out["G"].float().cpu(), fw["g"]),
+        "dx": Hn.max_rel(out["dx"].float().cpu(), bw["dx"]),
+        "dW_gate": Hn.max_rel(out["dW_gate"].cpu(), bw["dW_gate"]),
+        "dW_down": Hn.max_rel(out["dW_down"].cpu(), bw["dW_down"]),
+        "dU": Hn.max_rel(out["dU"].float().cpu(), bw["dU"]),
+    }
+    if save_H:
+        errs["H"] = Hn.max_rel(out["H"].float().cpu(), fw["h"])
+    U = Hn.check_integers(eg, inp["ids"].cpu().numpy())
+    errs["dE_rows"] = Hn.max_rel(eg["dE_rows"][:U].cpu(), oeg["dE_rows"])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, f"{shape.name} T={T}: over tolerance {tol}: {bad} (all: {errs})"
+
+    # one sparse AdamW step at the end of each side's own chain (GPU: its gradient rows;
+    # oracle: its own).  The moments are smooth in the gradient and carry its tolerance; the
+    # step-1 parameter update is lr*sign(g), so parameters are compared where the sign of g is
+    # beyond doubt, i.e. |g_ref| above the gradient's own error bound.
+    V, F = shape.vocab, shape.d_ff
+    dt = inp["E"].dtype
+    master = inp["E"].float().clone()
+    E = inp["E"].clone()
+    m = torch.zeros(V, F, dtype=torch.float32, device=DEV)
+    v = torch.zeros(V, F, dtype=torch.float32, device=DEV)
+    L.stem_embed_sparse_adamw(ctx, eg["uniq_ids"], eg["n_uniq"], eg["dE_rows"], E,
+                              master if dt == torch.bfloat16 else None, m, v, step=1, **Hn.ADAMW)
+    L.stem_sync_status(ctx)
+    p_ref, m_ref, v_ref = O.sparse_adamw(oeg["uniq_ids"], oeg["dE_rows"], inputs.to_f64(inp["E"]),
+                                         np.zeros((V, F)), np.zeros((V, F)), step=1, **Hn.ADAMW)
+    p_gpu = (master if dt == torch.bfloat16 else E).cpu().numpy()
+    assert Hn.max_rel(m.cpu().numpy(), m_ref) <= tol
+    assert Hn.max_rel(v.cpu().numpy(), v_ref) <= 2 * tol
+    uniq = oeg["uniq_ids"]
+    sure = np.abs(oeg["dE_rows"]) > 2 * tol * np.abs(oeg["dE_rows"]).max()
+    assert sure.mean() > 0.5
+    diff = np.abs(p_gpu[uniq] - p_ref[uniq])[sure].max() / np.abs(p_ref).max()
+    assert diff <= 1e-5, diff
+    untouched = np.setdiff1d(np.arange(V), uniq)
+    np.testing.assert_array_equal(p_gpu[untouched], inp["E"].float().cpu().numpy()[untouched])
+    ut = torch.from_numpy(untouched).to(DEV)
+    assert not m[ut].any() and not v[ut].any()
+    if dt == torch.bfloat16:
+        np.testing.assert_array_equal(E[ut].cpu().view(torch.int16).numpy(), inp["E"][ut].cpu().view(torch.int16).numpy())
+    ctx.close()
+    return errs
+
+
+def test_c1_tiny_fp32_full_pipeline():
+    s = inputs.SHAPES["C1"]
+    errs = _pipeline_case(s, s.tokens, seed=1)
+    print("C1 errors", errs)
+
+
+@pytest.mark.parametrize("T", [1, 63, 200])
+def test_fp32_ragged_token_counts(T):
+    s = inputs.StemShape("f32-ragged", 72, 132, 301, 1, T, "f32")
+    _pipeline_case(s, T, seed=2)
+
+
+@pytest.mark.parametrize("T,d,F", [(600, 192, 576), (257, 64, 64), (1, 128, 320), (1100, 512, 256)])
+def test_bf16_several_tiles_and_ragged_tails(T, d, F):
+    # 256-wide tiles: these sizes give full tiles plus a ragged last tile in every dimension
+    s = inputs.StemShape("bf16-ragged", d, F, 1000, 1, T, "bf16")
+    _pipeline_case(s, T, seed=3)
+
+
+def test_bf16_backward_recomputes_h_when_not_saved():
+    s = inputs.StemShape("bf16-noH", 128, 384, 500, 1, 300, "bf16")
+    _pipeline_case(s, 300, seed=4, save_H=False)
+
+
+def test_bf16_all_tokens_same_id_and_all_distinct():
+    s = inputs.StemShape("bf16-ids", 64, 128, 700, 1, 520, "bf16")
+    _pipeline_case(s, 520, seed=5, ids=np.full(520, 699, np.int32))
+    _pipeline_case(s, 520, seed=6, ids=np.random.default_rng(0).permutation(700)[:520].astype(np.int32))
+
+
+@pytest.mark.parametrize("T,V", [(1, 1), (2, 2), (64, 5), (4096, 50304), (4097, 128256), (16384, 128256),
+                                 (65536, 128256), (70001, 64), (5000, (1 << 20) + 3)])
+def test_sort_unique_offsets_bit_exact(T, V):
+    ids = inputs.zipf_ids(T, V, seed=T + V)
+    s = inputs.StemShape("ints", 64, 64, V, 1, T, "bf16")
+    ctx = Hn.make_ctx(s, T)
+    eg = Hn.hip_embed_grad(ctx, torch.from_numpy(ids).to(DEV), None, V, with_rows=False)
+    L.stem_sync_status(ctx)
+    Hn.check_integers(eg, ids)
+    ctx.close()
+
+
+def test_segmented_sum_is_bit_reproducible_and_conserves_column_sums():
+    s = inputs.StemShape("det", 64, 2112, 3000, 1, 9000, "bf16")
+    ids = torch.from_numpy(inputs.zipf_ids(9000, 3000, seed=9)).to(DEV)
+    dU = inputs.normal((9000, 2112), 1.0, 10, torch.bfloat16, DEV)
+    ctx = Hn.make_ctx(s, 9000)
+    a = Hn.hip_embed_grad(ctx, ids, dU, 3000)
+    b = Hn.hip_embed_grad(ctx, ids, dU, 3000)
+    U = int(a["n_uniq"].item())
+    assert torch.equal(a["dE_rows"][:U], b["dE_rows"][:U])
+    ref = O.embed_grad(ids.cpu().numpy(), inputs.to_f64(dU))
+    assert Hn.max_rel(a["dE_rows"][:U].cpu(), ref["dE_rows"]) <= 1e-5
+    col = a["dE_rows"][:U].double().sum(0).cpu().numpy()
+    assert Hn.max_rel(col, inputs.to_f64(dU).sum(0)) <= 1e-5
+    ctx.close()
+
+
+def test_whole_backward_is_bit_reproducible():
+    s = inputs.StemShape("det2", 128, 256, 400, 1, 700, "bf16")
+    inp = inputs.layer_inputs(s, 11, device=DEV, tokens=700)
+    ctx = Hn.make_ctx(s, 700)
+    a = Hn.hip_forward_backward(ctx, inp)
+    b = Hn.hip_forward_backward(ctx, inp)
+    for k in ("y", "dx", "dW_gate", "dW_down", "dU"):
+        assert torch.equal(a[k], b[k]), k
+    ctx.close()
+
+
+def test_weight_gradient_accumulate_flag():
+    s = inputs.StemShape("acc", 64, 128, 100, 1, 90, "bf16")
+    inp = inputs.layer_inputs(s, 12, device=DEV, tokens=90)
+    ctx = Hn.make_ctx(s, 90)
+    out = Hn.hip_forward_backward(ctx, inp)
+    dWg = out["dW_gate"].clone()
+    dWd = out["dW_down"].clone()
+    L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], out["G"],
+                        out["H"], None, dWg, dWd, out["dU"], accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dWg, out["dW_gate"] * 2) and torch.equal(dWd, out["dW_down"] * 2)
+    ctx.close()
+
+
+def test_edge_cases_and_error_reporting():
+    s = inputs.SHAPES["C1"]
+    inp = inputs.layer_inputs(s, 13, device=DEV)
+    ctx = Hn.make_ctx(s, s.tokens)
+    T, d, F = s.tokens, s.d_model, s.d_ff
+    y = torch.full((T, d), 7.0, device=DEV)
+    # T = 0 is a no-op
+    L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], y, T=0)
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())
+    eg = Hn.hip_embed_grad(ctx, inp["ids"][:0], None, s.vocab, with_rows=False)
+    assert int(eg["n_uniq"].item()) == 0 and int(eg["seg_offsets"][0].item()) == 0
+    # T beyond the context's capacity
+    with pytest.raises(L.StemError) as e:
+        L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], y, T=T + 1)
+    assert e.value.status == L.STEM_ERR_SHAPE
+    # null pointer
+    with pytest.raises(L.StemError) as e:
+        L.stem_ffn_forward(ctx, inp["x"], inp["ids"], None, inp["W_down"], inp["E"], y)
+    assert e.value.status == L.STEM_ERR_INVALID_ARG
+    # misaligned pointer
+    with pytest.raises(L.StemError) as e:
+        L.stem_ffn_forward(ctx, inp["x"].flatten()[1:], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], y, T=1)
+    assert e.value.status == L.STEM_ERR_INVALID_ARG
+    # id out of range: no fault, sticky flag reported at the next synchronising status call
+    bad = inp["ids"].clone()
+    bad[5] = s.vocab
+    bad[9] = -3
+    L.stem_ffn_forward(ctx, inp["x"], bad, inp["W_gate"], inp["W_down"], inp["E"], y)
+    with pytest.raises(L.StemError) as e:
+        L.stem_sync_status(ctx)
+    assert e.value.status == L.STEM_ERR_ID_RANGE
+    L.stem_sync_status(ctx)  # flag was cleared
+    # unsupported widths are refused at creation
+    with pytest.raises(L.StemError) as e:
+        L.stem_create(100, 256, 10, L.STEM_BF16, 8, 0)
+    assert e.value.status == L.STEM_ERR_UNSUPPORTED
+    ctx.close()
+
+
+def test_id_at_last_row_of_table():
+    s = inputs.StemShape("lastrow", 64, 64, 33, 1, 40, "bf16")
+    ids = np.full(40, 32, np.int32)
+    ids[::3] = 0
+    _pipeline_case(s, 40, seed=14, ids=ids)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sparse_adamw_three_steps_on_shared_gradients(dtype):
+    # Both sides receive the same seeded gradient rows and row list, so the comparison is tight.
+    V, F, T = 777, 320, 400
+    s = inputs.StemShape("adamw", 64, F, V, 1, T, dtype)
+    ctx = Hn.make_ctx(s, T)
+    dt = inputs.torch_dtype(dtype)
+    E = inputs.normal((V, F), 0.02, 30, dt, DEV)
+    E0 = E.clone()
+    master = E.float().clone()
+    m = torch.zeros(V, F, dtype=torch.float32, device=DEV)
+    v = torch.zeros(V, F, dtype=torch.float32, device=DEV)
+    p_ref, m_ref, v_ref = inputs.to_f64(E), np.zeros((V, F)), np.zeros((V, F))
+    for step in (1, 2, 3):
+        uniq = np.unique(inputs.zipf_ids(T, V, seed=40 + step)).astype(np.int32)
+        U = len(uniq)
+        g = inputs.normal((T, F), 10.0 ** (step - 3), 50 + step, torch.float32, DEV)
+        g[0, :7] = 0.0  # exact zeros: the update must still be finite
+        d_uniq = torch.zeros(T, dtype=torch.int32, device=DEV)
+        d_uniq[:U] = torch.from_numpy(uniq).to(DEV)
+        n_uniq = torch.tensor([U], dtype=torch.int32, device=DEV)
+        L.stem_embed_sparse_adamw(ctx, d_uniq, n_uniq, g, E, master if dtype == "bf16" else None, m, v,
+                                  step=step, **Hn.ADAMW)
+        p_ref, m_ref, v_ref = O.sparse_adamw(uniq, g[:U].cpu().numpy(), p_ref, m_ref, v_ref, step=step, **Hn.ADAMW)
+    L.stem_sync_status(ctx)
+    p_gpu = (master if dtype == "bf16" else E).cpu().numpy()
+    assert np.isfinite(p_gpu).all()
+    assert Hn.max_rel(p_gpu, p_ref) <= 1e-5
+    assert Hn.max_rel(m.cpu().numpy(), m_ref) <= 1e-5
+    assert Hn.max_rel(v.cpu().numpy(), v_ref) <= 1e-5
+    if dtype == "bf16":
+        # working copy = master rounded to nearest-even bf16 on touched rows, untouched rows keep their bits
+        want = O.bf16_round(p_gpu)
+        touched = np.zeros(V, bool)
+        for step in (1, 2, 3):
+            touched[np.unique(inputs.zipf_ids(T, V, seed=40 + step))] = True
+        got = E.float().cpu().numpy().astype(np.float64)
+        np.testing.assert_array_equal(got[touched], want[touched])
+        np.testing.assert_array_equal(got[~touched], E0.float().cpu().numpy()[~touched])
+    ctx.close()
