@@ -2,80 +2,115 @@
 // for gfx950, with the layer's element-wise work fused into the epilogues.
 //
 // One kernel template computes  C[m,n] = sum_k Aop[m,k] * Bop[n,k]  on a 256x256
-// output tile per workgroup (4 wavefronts, each a 128x128 quadrant held as 4x4
-// accumulators of v_mfma_f32_32x32x16_bf16), stepping K by 64 through two LDS stages.
-// Either operand may be stored K-contiguous ([rows,K]) or rows-contiguous ([K,rows]);
-// the second kind is transposed 8x8 in registers on its way into LDS, so the MFMA
-// loop always reads 16-byte K-contiguous fragments from one LDS layout.
+// output tile per workgroup: 4 wavefronts, each a 128x128 quadrant held as 4x4
+// accumulators of v_mfma_f32_32x32x16_bf16, K stepped by 64 through two LDS stages.
 //
-// LDS tile layout: row r (an m or n index within the tile) owns 128 bytes = 8 chunks
-// of 8 bf16; chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7).  With that XOR a
-// ds_read_b128 of one chunk column over 16 consecutive rows touches all 64 banks once.
+// Operands.  "KC" = stored [rows,K] with K contiguous: tiles go global -> LDS directly
+// (buffer_load ... lds, 16 bytes per lane, whole 128-byte lines per row; half lines were
+// measured to halve the L1 rate).  "MC" = stored [K,rows] with rows contiguous: tiles go
+// through registers, are transposed 8x8 there and written to LDS, so the MFMA loop always
+// reads 16-byte K-contiguous fragments from one LDS layout.  All loads are buffer loads:
+// out-of-range rows / k read as zero, so ragged edges need no branches.
 //
-// The MFMA is issued with the N-side fragment as its row operand and the M-side
-// fragment as its column operand, so a lane ends up holding, for one m (token), groups
-// of 4 consecutive n (features): row-major outputs, the gathered table row and the
-// saved activations are then accessed 8 or 16 bytes at a time per lane.
+// LDS tile layout: row r (an m or n index within the tile) owns 128 bytes = 8 chunks of
+// 8 bf16; chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7).  With that XOR a
+// ds_read_b128 of one chunk column over 16 consecutive rows touches all 64 banks once
+// (SQ_LDS_BANK_CONFLICT reads 0 for this kernel).
+//
+// Schedule.  One iteration = one K tile = 4 k-steps of 16 MFMAs.  Fragments are double
+// buffered in registers: while the MFMAs of k-step s run, the 8 fragment reads of step
+// s+1 are issued between them.  The loads of the next tile are spread over the k-steps
+// (a vector-memory instruction blocks the issuing wavefront for tens of cycles, during
+// which its MFMA queue drains, so they are never issued back to back).  The single
+// barrier per iteration sits before the last k-step, so that step overlaps the first
+// fragment reads of the next stage.  The loop is unrolled by two so that every LDS
+// address is a loop-invariant register plus an immediate.
+//
+// Epilogue.  The MFMA is issued with the N-side fragment as its row operand, so a lane
+// holds, for one m, groups of 4 consecutive n.  Each wavefront stages its accumulators
+// through LDS (fp32, 32 rows at a time) and reads them back row-contiguous: 16 lanes
+// cover 128 consecutive n of one row, so the outputs, the gathered table row and the
+// saved activations are all accessed as 16-byte pieces of whole 128-byte lines.
 #include "stem_internal.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = 256 * BK * 2;  // one operand tile in LDS
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+constexpr uint32_t OOB = 0x80000000u;  // a buffer offset beyond any operand: reads as zero
 
 __device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
   return (uint32_t)(row * 128 + (((chunk ^ (row >> 1)) & 7) << 4));
 }
 
-// ---- global -> registers ----------------------------------------------------------
-// K-contiguous operand: thread t takes 16-byte chunk (t & 7) of rows (t >> 3) + 32 i.
-__device__ __forceinline__ void load_kc(const bf16_t* __restrict__ base, int ld, int row0, int rows,
-                                        int k0, int K, int tid, uint4 (&st)[8]) {
-  const int kc = tid & 7;
-  const int r = tid >> 3;
-  const bool kok = (k0 + kc * 8) < K;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = row0 + r + 32 * i;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (kok && row < rows) v = *reinterpret_cast<const uint4*>(base + (size_t)row * ld + k0 + kc * 8);
-    st[i] = v;
+// A buffer resource that moves along the operand: base advances, the record count shrinks.
+struct Window {
+  const char* base;
+  int64_t left;  // bytes from base to the end of the operand (may go negative)
+  __device__ __forceinline__ rsrc_t rsrc() const {
+    const int64_t l = left < 0 ? 0 : left;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, (int)(l > 0x7fffffff ? 0x7fffffff : l),
+                                             0x00020000);
   }
-}
-__device__ __forceinline__ void store_kc(char* tile, int tid, const uint4 (&st)[8]) {
-  const int kc = tid & 7;
-  const int r = tid >> 3;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(tile + lds_off(r + 32 * i, kc)) = st[i];
-}
+  __device__ __forceinline__ void advance(int64_t bytes) { base += bytes; left -= bytes; }
+};
 
-// rows-contiguous operand: thread t owns the 8(k) x 8(rows) block kb = t & 7, rb = t >> 3.
-__device__ __forceinline__ void load_mc(const bf16_t* __restrict__ base, int ld, int row0, int rows,
-                                        int k0, int K, int tid, uint4 (&st)[8]) {
-  const int kb = tid & 7;
-  const int rb = tid >> 3;
-  const bool rok = (row0 + rb * 8) < rows;
+// ---- KC operand: global -> LDS direct -----------------------------------------------
+// Wavefront w loads row groups g = w*8 + i (8 rows each); lane -> row g*8 + (lane >> 3),
+// chunk slot lane & 7; the lane fetches the chunk that belongs in its slot.
+struct LoaderKC {
+  uint32_t off[8];
+  Window win;
+  __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int row0, int wave, int lane) {
+    win.base = reinterpret_cast<const char*>(p);
+    win.left = (int64_t)rows * ld * 2;
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    const int k = k0 + kb * 8 + kk;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (rok && k < K) v = *reinterpret_cast<const uint4*>(base + (size_t)k * ld + row0 + rb * 8);
-    st[kk] = v;
+    for (int i = 0; i < 8; ++i) {
+      const int row = (wave * 8 + i) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((row >> 1) & 7);
+      off[i] = (row0 + row) < rows ? (uint32_t)(((int64_t)(row0 + row) * ld + c * 8) * 2) : OOB;
+    }
   }
-}
-__device__ __forceinline__ uint32_t pick(const uint4& v, int q) {
-  return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
-}
-__device__ __forceinline__ void store_mc(char* tile, int tid, const uint4 (&st)[8]) {
-  const int kb = tid & 7;
-  const int rb = tid >> 3;
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
+  // load i (0..7) of the tile the window points at, into `tile` (LDS, wave-uniform)
+  __device__ __forceinline__ void issue(int i, char* tile, int wave) const {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(win.rsrc(), (lds_ptr_t)(tile + (wave * 8 + i) * 1024), 16, off[i], 0, 0,
+                                             0);
+  }
+  __device__ __forceinline__ void next_tile() { win.advance(BK * 2); }
+};
+
+// ---- MC operand: global -> registers -> 8x8 transpose -> LDS ---------------------------
+// Thread t owns the 8(k) x 8(rows) block kb = t & 7, rb = t >> 3 of the 64 x 256 tile.
+struct LoaderMC {
+  uint32_t off0;
+  uint32_t ld2;
+  Window win;
+  uint4 st[8];
+  __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int K, int row0, int tid) {
+    win.base = reinterpret_cast<const char*>(p);
+    win.left = (int64_t)K * ld * 2;
+    ld2 = (uint32_t)ld * 2;
+    const int kb = tid & 7, rb = tid >> 3;
+    off0 = (row0 + rb * 8) < rows ? (uint32_t)(((int64_t)kb * 8 * ld + row0 + rb * 8) * 2) : OOB;
+  }
+  __device__ __forceinline__ void issue(int kk) {
+    const uint32_t o = off0 == OOB ? OOB : off0 + kk * ld2;
+    st[kk] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(win.rsrc(), o, 0, 0));
+  }
+  __device__ __forceinline__ void next_tile() { win.advance((int64_t)BK * ld2); }
+  static __device__ __forceinline__ uint32_t pick(const uint4& v, int q) {
+    return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
+  }
+  // rows r of this thread's block, transposed so that k runs along the 16-byte chunk
+  __device__ __forceinline__ void commit(int r, char* tile, int tid) const {
+    const int kb = tid & 7, rb = tid >> 3;
     const int q = r >> 1;
     uint32_t w[4];
 #pragma unroll
@@ -85,33 +120,23 @@ __device__ __forceinline__ void store_mc(char* tile, int tid, const uint4 (&st)[
     }
     *reinterpret_cast<uint4*>(tile + lds_off(rb * 8 + r, kb)) = make_uint4(w[0], w[1], w[2], w[3]);
   }
-}
-
-template <int L>
-__device__ __forceinline__ void load_op(const bf16_t* base, int ld, int row0, int rows, int k0, int K,
-                                        int tid, uint4 (&st)[8]) {
-  if (L == OP_KC) load_kc(base, ld, row0, rows, k0, K, tid, st);
-  else load_mc(base, ld, row0, rows, k0, K, tid, st);
-}
-template <int L>
-__device__ __forceinline__ void store_op(char* tile, int tid, const uint4 (&st)[8]) {
-  if (L == OP_KC) store_kc(tile, tid, st);
-  else store_mc(tile, tid, st);
-}
+};
 
 // ---- epilogue math ------------------------------------------------------------------
-__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ float sigmoidf_fast(float z) {
-  return __builtin_amdgcn_rcpf(1.0f + __expf(-z));
+__device__ __forceinline__ float sigmoidf_fast(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  bf16x8_t v;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) v[q] = (__bf16)f[q];
+  return __builtin_bit_cast(uint4, v);
 }
-__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
-  bf16x4_t v;
-  v[0] = (__bf16)a; v[1] = (__bf16)b; v[2] = (__bf16)c; v[3] = (__bf16)d;
-  return *reinterpret_cast<uint2*>(&v);
-}
-__device__ __forceinline__ void unpack4(uint2 u, float (&f)[4]) {
-  f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
-  f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
+__device__ __forceinline__ void unpack8(uint4 u, float (&f)[8]) {
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    f[2 * q] = __uint_as_float(w[q] << 16);
+    f[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+  }
 }
 
 // Workgroup -> output tile.  Consecutive workgroup ids go round-robin over the 8 XCDs,
@@ -136,7 +161,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE_BYTES];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int ntm = (p.M + BM - 1) / BM, ntn = (p.N + BN - 1) / BN;
   int tm, tn;
@@ -151,108 +176,216 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  uint4 sa[8], sb[8];
-  const int nk = (p.K + BK - 1) / BK;
-  load_op<LA>(p.A, p.lda, m0, p.M, 0, p.K, tid, sa);
-  load_op<LB>(p.B, p.ldb, n0, p.N, 0, p.K, tid, sb);
-  store_op<LA>(smem, tid, sa);
-  store_op<LB>(smem + TILE_BYTES, tid, sb);
-  __syncthreads();
+  LoaderKC ka, kb_;
+  LoaderMC ma, mb;
+  if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane); else ma.init(p.A, p.lda, p.M, p.K, m0, tid);
+  if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane); else mb.init(p.B, p.ldb, p.N, p.K, n0, tid);
 
-  const int frow = lane & 31;
-  const int fk = lane >> 5;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    const bool more = (kt + 1) < nk;
-    if (more) {
-      load_op<LA>(p.A, p.lda, m0, p.M, (kt + 1) * BK, p.K, tid, sa);
-      load_op<LB>(p.B, p.ldb, n0, p.N, (kt + 1) * BK, p.K, tid, sb);
-    }
-    const char* tA = smem + cur * STAGE_BYTES;
-    const char* tB = tA + TILE_BYTES;
+  // fragment addresses: per k-step one register per operand and stage, rows via immediates
+  const int frow = lane & 31, fk = lane >> 5;
+  uint32_t fa_addr[2][4], fb_addr[2][4];
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      bf16x8_t fa[4], fb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8_t*>(tA + lds_off(wm * 128 + i * 32 + frow, ks * 2 + fk));
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8_t*>(tB + lds_off(wn * 128 + j * 32 + frow, ks * 2 + fk));
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+      const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ (frow >> 1)) & 7) << 4);
+      fa_addr[s][ks] = (uint32_t)(s * STAGE_BYTES + (wm * 128 + frow) * 128) + sw;
+      fb_addr[s][ks] = (uint32_t)(s * STAGE_BYTES + TILE_BYTES + (wn * 128 + frow) * 128) + sw;
     }
-    if (more) {
-      char* nA = smem + (cur ^ 1) * STAGE_BYTES;
-      store_op<LA>(nA, tid, sa);
-      store_op<LB>(nA + TILE_BYTES, tid, sb);
-    }
-    __syncthreads();
-  }
 
-  // ---- epilogue: lane holds token m = .. + (lane & 31); for accumulator (i,j), register
-  // group g (4 registers) covers features  j*32 + g*8 + (lane >> 5)*4 + {0,1,2,3}.
+  // fragment q (0..7) of a k-step, in load order a0,b0,b1,a1,b2,b3,a2,a3
+  auto rfrag1 = [&](int stage, int ks, int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
+    constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
+    constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
+    if (isA[q]) fa[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + fa_addr[stage][ks] + idx[q] * 4096);
+    else fb[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + fb_addr[stage][ks] + idx[q] * 4096);
+  };
+  // MFMA pair q (0..7), in an order that consumes fragments in the order they were read
+  auto mma2 = [&](int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
+    constexpr int ii[16] = {0, 0, 1, 1, 0, 1, 0, 1, 2, 2, 2, 2, 3, 3, 3, 3};
+    constexpr int jj[16] = {0, 1, 0, 1, 2, 2, 3, 3, 0, 1, 2, 3, 0, 1, 2, 3};
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int i = ii[2 * q + u], j = jj[2 * q + u];
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  // Loads of the next tile, by slot: `phase` 3 = after the barrier (last k-step of the
+  // previous iteration), 0..2 = k-steps of this iteration; q = position within the k-step.
+  // Register-staged (MC) operands are fetched first so their data can be transposed and
+  // written to LDS in k-step 2, while direct-to-LDS loads may still be in flight.
+  auto issue_loads = [&](int phase, int q, char* next_stage) {
+    if (LA == OP_KC && LB == OP_KC) {        // 16 direct loads: 8 in phase 3, 4 + 4 in phases 0, 1
+      int n = -1;
+      if (phase == 3) n = q; else if (phase == 0 && q < 4) n = 8 + q; else if (phase == 1 && q < 4) n = 12 + q;
+      if (n >= 0) { if (n & 1) kb_.issue(n >> 1, next_stage + TILE_BYTES, wave); else ka.issue(n >> 1, next_stage, wave); }
+    } else if (LA == OP_KC && LB == OP_MC) {  // B through registers in phase 3, A direct in phases 0, 1
+      if (phase == 3) mb.issue(q);
+      else if (phase == 0 && q < 4) ka.issue(q, next_stage, wave);
+      else if (phase == 1 && q < 4) ka.issue(4 + q, next_stage, wave);
+    } else {                                  // both through registers: A in phase 3, B in phase 0
+      if (phase == 3) ma.issue(q);
+      else if (phase == 0) mb.issue(q);
+    }
+  };
+  // Register-staged operands go to LDS during k-step 2 (their loads were the oldest issued).
+  auto commit_regs = [&](int q, char* next_stage) {
+    if (LA == OP_KC && LB == OP_MC) {
+      if (q == 0) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      mb.commit(q, next_stage + TILE_BYTES, tid);
+    } else if (LA == OP_MC && LB == OP_MC) {
+      if (q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      ma.commit(q, next_stage, tid);
+      mb.commit(q, next_stage + TILE_BYTES, tid);
+    }
+  };
+  auto advance = [&]() {
+    if (LA == OP_KC) ka.next_tile(); else ma.next_tile();
+    if (LB == OP_KC) kb_.next_tile(); else mb.next_tile();
+  };
+
+  const int nk = (p.K + BK - 1) / BK;
+  // ---- prologue: tile 0 into stage 0 -------------------------------------------------
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    if (LA == OP_KC) ka.issue(q, smem, wave); else ma.issue(q);
+    if (LB == OP_KC) kb_.issue(q, smem + TILE_BYTES, wave); else mb.issue(q);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    if (LA == OP_MC) ma.commit(q, smem, tid);
+    if (LB == OP_MC) mb.commit(q, smem + TILE_BYTES, tid);
+  }
+  advance();
+  __syncthreads();
+  bf16x8_t xa[4], xb[4], ya[4], yb[4];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) rfrag1(0, 0, q, xa, xb);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) issue_loads(3, q, smem + STAGE_BYTES);
+
+  // ---- main loop, two K tiles per trip (stage 0 then stage 1) --------------------------
+  auto iteration = [&](const int st) __attribute__((always_inline)) {
+    char* next_stage = smem + (st ^ 1) * STAGE_BYTES;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag1(st, 1, q, ya, yb);
+      issue_loads(0, q, next_stage);
+      mma2(q, xa, xb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag1(st, 2, q, xa, xb);
+      issue_loads(1, q, next_stage);
+      mma2(q, ya, yb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag1(st, 3, q, ya, yb);
+      commit_regs(q, next_stage);
+      mma2(q, xa, xb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // next tile complete in LDS for every wavefront, and nobody still reads the stage
+    // that the loads after this barrier overwrite
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    advance();
+    char* after_next = smem + st * STAGE_BYTES;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag1(st ^ 1, 0, q, xa, xb);
+      issue_loads(3, q, after_next);
+      mma2(q, ya, yb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  for (int kt = 0; kt + 1 < nk; kt += 2) {
+    iteration(0);
+    iteration(1);
+  }
+  if (nk & 1) iteration(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  // ---- epilogue: per wavefront, 32 rows at a time through LDS ----------------------------
+  constexpr int SROW = 528;                   // staged row: 128 fp32 + 16 bytes of padding
+  char* stg = smem + wave * 32768;            // 32 x 528 = 16896 bytes used
+  const int srow = lane >> 4;                 // row within a group of 4
+  const int scol = (lane & 15) * 8;           // first of this lane's 8 consecutive columns
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int m = m0 + wm * 128 + i * 32 + frow;
-    if (m >= p.M) continue;
-    int id = 0;
-    if (EPI == EPI_GATE || EPI == EPI_DH) {
-      id = p.ids[m];
-      if ((unsigned)id >= (unsigned)p.E_rows) {
-        *p.flag = 1;
-        id = id < 0 ? 0 : p.E_rows - 1;
-      }
-    }
-    const size_t orow = (size_t)m * p.N;
-    const size_t erow = (size_t)id * p.N;
+    // accumulators -> LDS: lane holds row frow, columns j*32 + g*8 + fk*4 .. +3
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      const f32x16_t v = acc[i][j];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn * 128 + j * 32 + g * 8 + fk * 4;
-        if (n >= p.N) continue;
-        const float c0 = acc[i][j][4 * g + 0], c1 = acc[i][j][4 * g + 1];
-        const float c2 = acc[i][j][4 * g + 2], c3 = acc[i][j][4 * g + 3];
-        if (EPI == EPI_BF16) {
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + orow + n) = pack4(c0, c1, c2, c3);
-        } else if (EPI == EPI_F32) {
-          float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + orow + n);
-          float4 v = make_float4(c0, c1, c2, c3);
-          if (p.accumulate) {
-            const float4 o = *dst;
-            v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-          }
-          *dst = v;
-        } else if (EPI == EPI_GATE) {
-          float e[4];
-          unpack4(*reinterpret_cast<const uint2*>(p.E + erow + n), e);
-          const float c[4] = {c0, c1, c2, c3};
-          float h[4];
+        f32x4_t w = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+        *reinterpret_cast<f32x4_t*>(stg + frow * SROW + (j * 32 + g * 8 + fk * 4) * 4) = w;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll 2
+    for (int pass = 0; pass < 8; ++pass) {
+      const int r = pass * 4 + srow;
+      const int m = m0 + wm * 128 + i * 32 + r;
+      const int n = n0 + wn * 128 + scol;
+      const f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4);
+      const f32x4_t c1 = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4 + 16);
+      if (m >= p.M || n >= p.N) continue;
+      const float c[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+      const size_t o = (size_t)m * p.N + n;
+      if (EPI == EPI_BF16) {
+        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.C) + o) = pack8(c);
+      } else if (EPI == EPI_F32) {
+        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + o);
+        float4 v0 = make_float4(c[0], c[1], c[2], c[3]), v1 = make_float4(c[4], c[5], c[6], c[7]);
+        if (p.accumulate) {
+          const float4 o0 = dst[0], o1 = dst[1];
+          v0.x += o0.x; v0.y += o0.y; v0.z += o0.z; v0.w += o0.w;
+          v1.x += o1.x; v1.y += o1.y; v1.z += o1.z; v1.w += o1.w;
+        }
+        dst[0] = v0;
+        dst[1] = v1;
+      } else {
+        int id = p.ids[m];
+        if ((unsigned)id >= (unsigned)p.E_rows) {
+          *p.flag = 1;
+          id = id < 0 ? 0 : p.E_rows - 1;
+        }
+        float e[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.E + (size_t)id * p.N + n), e);
+        if (EPI == EPI_GATE) {
+          float h[8];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) h[q] = c[q] * sigmoidf_fast(c[q]) * e[q];
-          if (p.outG) *reinterpret_cast<uint2*>(p.outG + orow + n) = pack4(c0, c1, c2, c3);
-          *reinterpret_cast<uint2*>(p.outH + orow + n) = pack4(h[0], h[1], h[2], h[3]);
+          for (int q = 0; q < 8; ++q) h[q] = c[q] * sigmoidf_fast(c[q]) * e[q];
+          if (p.outG) *reinterpret_cast<uint4*>(p.outG + o) = pack8(c);
+          *reinterpret_cast<uint4*>(p.outH + o) = pack8(h);
         } else {  // EPI_DH
-          float e[4], gz[4];
-          unpack4(*reinterpret_cast<const uint2*>(p.E + erow + n), e);
-          unpack4(*reinterpret_cast<const uint2*>(p.inG + orow + n), gz);
-          const float c[4] = {c0, c1, c2, c3};
-          float du[4], dg[4];
+          float gz[8], du[8], dg[8];
+          unpack8(*reinterpret_cast<const uint4*>(p.inG + o), gz);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
+          for (int q = 0; q < 8; ++q) {
             const float sg = sigmoidf_fast(gz[q]);
             du[q] = c[q] * gz[q] * sg;
             dg[q] = c[q] * e[q] * sg * (1.0f + gz[q] * (1.0f - sg));
           }
-          *reinterpret_cast<uint2*>(p.outdU + orow + n) = pack4(du[0], du[1], du[2], du[3]);
-          *reinterpret_cast<uint2*>(p.outdG + orow + n) = pack4(dg[0], dg[1], dg[2], dg[3]);
+          *reinterpret_cast<uint4*>(p.outdU + o) = pack8(du);
+          *reinterpret_cast<uint4*>(p.outdG + o) = pack8(dg);
         }
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
 }
 
@@ -268,6 +401,11 @@ hipError_t launch(stem_ctx* ctx, int kid, const GemmArgs& a, hipStream_t s) {
 
 hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
+  // buffer offsets are 32-bit: every operand must stay below 2 GiB
+  const int64_t lim = 0x7fffffff;
+  const int64_t abytes = (la == OP_KC ? (int64_t)a.M : (int64_t)a.K) * a.lda * 2;
+  const int64_t bbytes = (lb == OP_KC ? (int64_t)a.N : (int64_t)a.K) * a.ldb * 2;
+  if (abytes > lim || bbytes > lim) return hipErrorInvalidValue;
   if (la == OP_KC && lb == OP_KC) {
     if (epi == EPI_BF16) return launch<OP_KC, OP_KC, EPI_BF16>(ctx, kid, a, s);
     if (epi == EPI_GATE) return launch<OP_KC, OP_KC, EPI_GATE>(ctx, kid, a, s);
