@@ -318,8 +318,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   char* stg = smem + wave * 32768;            // 32 x 528 = 16896 bytes used
   const int srow = lane >> 4;                 // row within a group of 4
   const int scol = (lane & 15) * 8;           // first of this lane's 8 consecutive columns
+  const int n = n0 + wn * 128 + scol;
+  const bool n_ok = n < p.N;
+  const int n_ld = n_ok ? n : 0;              // in-bounds column for the prefetching loads
+  constexpr bool FUSED = (EPI == EPI_GATE || EPI == EPI_DH);
+
+  // Everything the element-wise part needs from memory is requested one 32-row block ahead
+  // (8 rows per lane and block), so the gathered table rows arrive while the previous block
+  // is being staged and stored.
+  uint4 ev[2][8], gv[2][8];
+  auto prefetch = [&](int i, int buf) __attribute__((always_inline)) {
+    if (!FUSED) return;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int m = m0 + wm * 128 + i * 32 + pass * 4 + srow;
+      const int mc = m < p.M ? m : p.M - 1;
+      int id = p.ids[mc];
+      if ((unsigned)id >= (unsigned)p.E_rows) {
+        *p.flag = 1;
+        id = id < 0 ? 0 : p.E_rows - 1;
+      }
+      ev[buf][pass] = *reinterpret_cast<const uint4*>(p.E + (size_t)id * p.N + n_ld);
+      if (EPI == EPI_DH) gv[buf][pass] = *reinterpret_cast<const uint4*>(p.inG + (size_t)mc * p.N + n_ld);
+    }
+  };
+  prefetch(0, 0);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
+    if (i + 1 < 4) prefetch(i + 1, (i + 1) & 1);
     // accumulators -> LDS: lane holds row frow, columns j*32 + g*8 + fk*4 .. +3
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -333,53 +359,53 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll 2
+#pragma unroll
     for (int pass = 0; pass < 8; ++pass) {
       const int r = pass * 4 + srow;
       const int m = m0 + wm * 128 + i * 32 + r;
-      const int n = n0 + wn * 128 + scol;
       const f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4);
       const f32x4_t c1 = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4 + 16);
-      if (m >= p.M || n >= p.N) continue;
       const float c[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+      const bool ok = n_ok && m < p.M;
       const size_t o = (size_t)m * p.N + n;
       if (EPI == EPI_BF16) {
-        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.C) + o) = pack8(c);
+        if (ok) *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.C) + o) = pack8(c);
       } else if (EPI == EPI_F32) {
-        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + o);
-        float4 v0 = make_float4(c[0], c[1], c[2], c[3]), v1 = make_float4(c[4], c[5], c[6], c[7]);
-        if (p.accumulate) {
-          const float4 o0 = dst[0], o1 = dst[1];
-          v0.x += o0.x; v0.y += o0.y; v0.z += o0.z; v0.w += o0.w;
-          v1.x += o1.x; v1.y += o1.y; v1.z += o1.z; v1.w += o1.w;
+        if (ok) {
+          float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + o);
+          float4 v0 = make_float4(c[0], c[1], c[2], c[3]), v1 = make_float4(c[4], c[5], c[6], c[7]);
+          if (p.accumulate) {
+            const float4 o0 = dst[0], o1 = dst[1];
+            v0.x += o0.x; v0.y += o0.y; v0.z += o0.z; v0.w += o0.w;
+            v1.x += o1.x; v1.y += o1.y; v1.z += o1.z; v1.w += o1.w;
+          }
+          dst[0] = v0;
+          dst[1] = v1;
         }
-        dst[0] = v0;
-        dst[1] = v1;
       } else {
-        int id = p.ids[m];
-        if ((unsigned)id >= (unsigned)p.E_rows) {
-          *p.flag = 1;
-          id = id < 0 ? 0 : p.E_rows - 1;
-        }
         float e[8];
-        unpack8(*reinterpret_cast<const uint4*>(p.E + (size_t)id * p.N + n), e);
+        unpack8(ev[i & 1][pass], e);
         if (EPI == EPI_GATE) {
           float h[8];
 #pragma unroll
           for (int q = 0; q < 8; ++q) h[q] = c[q] * sigmoidf_fast(c[q]) * e[q];
-          if (p.outG) *reinterpret_cast<uint4*>(p.outG + o) = pack8(c);
-          *reinterpret_cast<uint4*>(p.outH + o) = pack8(h);
+          if (ok) {
+            if (p.outG) *reinterpret_cast<uint4*>(p.outG + o) = pack8(c);
+            *reinterpret_cast<uint4*>(p.outH + o) = pack8(h);
+          }
         } else {  // EPI_DH
           float gz[8], du[8], dg[8];
-          unpack8(*reinterpret_cast<const uint4*>(p.inG + o), gz);
+          unpack8(gv[i & 1][pass], gz);
 #pragma unroll
           for (int q = 0; q < 8; ++q) {
             const float sg = sigmoidf_fast(gz[q]);
             du[q] = c[q] * gz[q] * sg;
             dg[q] = c[q] * e[q] * sg * (1.0f + gz[q] * (1.0f - sg));
           }
-          *reinterpret_cast<uint4*>(p.outdU + o) = pack8(du);
-          *reinterpret_cast<uint4*>(p.outdG + o) = pack8(dg);
+          if (ok) {
+            *reinterpret_cast<uint4*>(p.outdU + o) = pack8(du);
+            *reinterpret_cast<uint4*>(p.outdG + o) = pack8(dg);
+          }
         }
       }
     }
