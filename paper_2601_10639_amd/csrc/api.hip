@@ -19,7 +19,8 @@ char g_create_err[512] = "";
 const char* const kKernelNames[K_COUNT_] = {
     "gemm_gate_fused", "gemm_gate_plain", "gemm_down",    "gemm_dh_fused", "gemm_dx",      "gemm_dw_down",
     "gemm_dw_gate",    "silu_gather",     "dh_epilogue",  "sort_count",    "sort_scan",    "sort_scatter",
-    "sort_fused",      "unique",          "seg_reduce",   "seg_combine",   "sparse_adamw", "row_copy"};
+    "sort_fused",      "unique",          "seg_reduce",   "seg_combine",   "sparse_adamw", "row_copy",
+    "transpose"};
 
 stem_status fail(stem_ctx* c, stem_status st, const char* fmt, ...) {
   char* buf = c ? c->err : g_create_err;
@@ -69,6 +70,7 @@ void release(stem_ctx* c) {
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
   (void)hipFree(c->H_ws); (void)hipFree(c->dG_ws); (void)hipFree(c->dH_ws);
+  (void)hipFree(c->WT_ws); (void)hipFree(c->actT_ws);
   for (int i = 0; i < 2; ++i) { (void)hipFree(c->sort_keys[i]); (void)hipFree(c->sort_vals[i]); }
   (void)hipFree(c->sort_counts); (void)hipFree(c->seg_of); (void)hipFree(c->seg_part);
   (void)hipFree(c->uniq_dev);
@@ -134,6 +136,10 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
   ok(hipMalloc(&c->H_ws, std::max<size_t>(TF * es, 16)));
   ok(hipMalloc(&c->dG_ws, std::max<size_t>(TF * es, 16)));
   if (desc->dtype == STEM_F32) ok(hipMalloc(&c->dH_ws, std::max<size_t>(TF * 4, 16)));
+  if (desc->dtype == STEM_BF16) {
+    ok(hipMalloc(&c->WT_ws, (size_t)desc->d_ff * desc->d_model * 2));
+    ok(hipMalloc(&c->actT_ws, std::max<size_t>((size_t)desc->d_model * ((max_tokens + 63) / 64 * 64) * 2, 16)));
+  }
   for (int i = 0; i < 2; ++i) {
     ok(dmalloc(&c->sort_keys[i], (size_t)max_tokens));
     ok(dmalloc(&c->sort_vals[i], (size_t)max_tokens));
@@ -257,31 +263,40 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
     const bf16_t* dyb = static_cast<const bf16_t*>(dy);
     const bf16_t* Hb = static_cast<const bf16_t*>(H);
     bf16_t* dGb = static_cast<bf16_t*>(c->dG_ws);
-    {  // dH = dy W_down, fused into dU and dG
+    bf16_t* WT = static_cast<bf16_t*>(c->WT_ws);
+    bf16_t* actT = static_cast<bf16_t*>(c->actT_ws);
+    const int ldT = (int)((T + 63) / 64 * 64);
+    // The weight operands of the two activation-gradient products are needed K-contiguous:
+    // transposing a [d,F] matrix costs a few percent of the product it feeds.
+    {  // dH = dy W_down, fused into dU and dG;  W_down^T is [F,d]
+      HIP_TRY(c, stem_transpose_bf16(c, W_down, d, F, WT, d, s));
       GemmArgs a = {};
-      a.A = dyb; a.lda = d; a.B = static_cast<const bf16_t*>(W_down); a.ldb = F;
+      a.A = dyb; a.lda = d; a.B = WT; a.ldb = d;
       a.M = (int)T; a.N = F; a.K = d;
       a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows; a.flag = c->flag;
       a.inG = static_cast<const bf16_t*>(saved_G); a.outdU = static_cast<bf16_t*>(dU); a.outdG = dGb;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_MC, EPI_DH, a, s));
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_KC, EPI_DH, a, s));
     }
-    {  // dW_down[d,F] = dy^T H
+    {  // dW_down[d,F] = dy^T H;  dy^T is [d, ldT] with zero padding along T
+      HIP_TRY(c, stem_transpose_bf16(c, dy, (int)T, d, actT, ldT, s));
       GemmArgs a = {};
-      a.A = dyb; a.lda = d; a.B = Hb; a.ldb = F;
-      a.M = d; a.N = F; a.K = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_MC, OP_MC, EPI_F32, a, s));
+      a.A = actT; a.lda = ldT; a.B = Hb; a.ldb = F;
+      a.M = d; a.N = F; a.K = ldT; a.K_mc = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_KC, OP_MC, EPI_F32, a, s));
     }
-    if (dx) {  // dx = dG W_gate
+    if (dx) {  // dx = dG W_gate;  W_gate^T is [d,F]
+      HIP_TRY(c, stem_transpose_bf16(c, W_gate, F, d, WT, F, s));
       GemmArgs a = {};
-      a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(W_gate); a.ldb = d;
+      a.A = dGb; a.lda = F; a.B = WT; a.ldb = F;
       a.M = (int)T; a.N = d; a.K = F; a.C = dx; a.flag = c->flag;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_MC, EPI_BF16, a, s));
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_KC, EPI_BF16, a, s));
     }
-    {  // dW_gate[F,d] = dG^T x
+    {  // dW_gate[F,d] = dG^T x = (x^T dG)^T: computed as [F,d] with A = dG (rows-contiguous), B = x^T
+      HIP_TRY(c, stem_transpose_bf16(c, x, (int)T, d, actT, ldT, s));
       GemmArgs a = {};
-      a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(x); a.ldb = d;
-      a.M = F; a.N = d; a.K = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_MC, EPI_F32, a, s));
+      a.A = dGb; a.lda = F; a.B = actT; a.ldb = ldT;
+      a.M = F; a.N = d; a.K = ldT; a.K_mc = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_KC, EPI_F32, a, s));
     }
   } else {
     const float* dyf = static_cast<const float*>(dy);

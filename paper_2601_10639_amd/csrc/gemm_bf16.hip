@@ -178,8 +178,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
 
   LoaderKC ka, kb_;
   LoaderMC ma, mb;
-  if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane); else ma.init(p.A, p.lda, p.M, p.K, m0, tid);
-  if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane); else mb.init(p.B, p.ldb, p.N, p.K, n0, tid);
+  if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane); else ma.init(p.A, p.lda, p.M, p.K_mc > 0 ? p.K_mc : p.K, m0, tid);
+  if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane); else mb.init(p.B, p.ldb, p.N, p.K_mc > 0 ? p.K_mc : p.K, n0, tid);
 
   // fragment addresses: per k-step one register per operand and stage, rows via immediates
   const int frow = lane & 31, fk = lane >> 5;
@@ -224,6 +224,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       if (phase == 3) mb.issue(q);
       else if (phase == 0 && q < 4) ka.issue(q, next_stage, wave);
       else if (phase == 1 && q < 4) ka.issue(4 + q, next_stage, wave);
+    } else if (LA == OP_MC && LB == OP_KC) {  // A through registers in phase 3, B direct in phases 0, 1
+      if (phase == 3) ma.issue(q);
+      else if (phase == 0 && q < 4) kb_.issue(q, next_stage + TILE_BYTES, wave);
+      else if (phase == 1 && q < 4) kb_.issue(4 + q, next_stage + TILE_BYTES, wave);
     } else {                                  // both through registers: A in phase 3, B in phase 0
       if (phase == 3) ma.issue(q);
       else if (phase == 0) mb.issue(q);
@@ -234,6 +238,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     if (LA == OP_KC && LB == OP_MC) {
       if (q == 0) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
       mb.commit(q, next_stage + TILE_BYTES, tid);
+    } else if (LA == OP_MC && LB == OP_KC) {
+      if (q == 0) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      ma.commit(q, next_stage, tid);
     } else if (LA == OP_MC && LB == OP_MC) {
       if (q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       ma.commit(q, next_stage, tid);
@@ -429,15 +436,20 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
   // buffer offsets are 32-bit: every operand must stay below 2 GiB
   const int64_t lim = 0x7fffffff;
-  const int64_t abytes = (la == OP_KC ? (int64_t)a.M : (int64_t)a.K) * a.lda * 2;
-  const int64_t bbytes = (lb == OP_KC ? (int64_t)a.N : (int64_t)a.K) * a.ldb * 2;
+  const int64_t kmc = a.K_mc > 0 ? a.K_mc : a.K;
+  const int64_t abytes = (la == OP_KC ? (int64_t)a.M : kmc) * a.lda * 2;
+  const int64_t bbytes = (lb == OP_KC ? (int64_t)a.N : kmc) * a.ldb * 2;
   if (abytes > lim || bbytes > lim) return hipErrorInvalidValue;
   if (la == OP_KC && lb == OP_KC) {
     if (epi == EPI_BF16) return launch<OP_KC, OP_KC, EPI_BF16>(ctx, kid, a, s);
     if (epi == EPI_GATE) return launch<OP_KC, OP_KC, EPI_GATE>(ctx, kid, a, s);
+    if (epi == EPI_DH) return launch<OP_KC, OP_KC, EPI_DH>(ctx, kid, a, s);
   } else if (la == OP_KC && lb == OP_MC) {
     if (epi == EPI_BF16) return launch<OP_KC, OP_MC, EPI_BF16>(ctx, kid, a, s);
     if (epi == EPI_DH) return launch<OP_KC, OP_MC, EPI_DH>(ctx, kid, a, s);
+    if (epi == EPI_F32) return launch<OP_KC, OP_MC, EPI_F32>(ctx, kid, a, s);
+  } else if (la == OP_MC && lb == OP_KC) {
+    if (epi == EPI_F32) return launch<OP_MC, OP_KC, EPI_F32>(ctx, kid, a, s);
   } else if (la == OP_MC && lb == OP_MC) {
     if (epi == EPI_F32) return launch<OP_MC, OP_MC, EPI_F32>(ctx, kid, a, s);
   }

@@ -27,6 +27,7 @@ enum StemKernelId {
   K_SEG_COMBINE,
   K_ADAMW,
   K_ROW_COPY,        // host-resident rows -> compact device table
+  K_TRANSPOSE,       // bf16 operand transposes ahead of the backward GEMMs
   K_COUNT_
 };
 
@@ -42,6 +43,8 @@ struct stem_ctx {
   void* H_ws;            // [max_tokens, F] context dtype
   void* dG_ws;           // [max_tokens, F] context dtype
   void* dH_ws;           // [max_tokens, F] fp32, STEM_F32 only
+  void* WT_ws;           // [F*d] bf16: a weight matrix transposed (backward)
+  void* actT_ws;         // [d, round_up(max_tokens, 64)] bf16: dy or x transposed (backward)
   int32_t* sort_keys[2]; // [max_tokens]
   int32_t* sort_vals[2]; // [max_tokens]
   int32_t* sort_counts;  // [64 * waves]
@@ -101,6 +104,7 @@ struct GemmArgs {
   const bf16_t* A; // M-side operand
   const bf16_t* B; // N-side operand
   int M, N, K;
+  int K_mc;        // k-rows that exist in a rows-contiguous operand (0 = K); the rest read as zero
   int lda, ldb;    // leading dimensions of the stored operands
   void* C;         // EPI_BF16 / EPI_F32 output, ld = N
   int accumulate;  // EPI_F32: add to C
@@ -121,6 +125,8 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
 // C[m,n] (+)= sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]
 hipError_t stem_sgemm(stem_ctx* ctx, int kid, const float* A, int64_t sam, int64_t sak, const float* B,
                       int64_t sbn, int64_t sbk, float* C, int M, int N, int K, int accumulate, hipStream_t s);
+// out[c,r] = in[r,c] (bf16), leading dimension ldo, zero padding beyond R
+hipError_t stem_transpose_bf16(stem_ctx* ctx, const void* in, int R, int C, void* out, int ldo, hipStream_t s);
 // H = SiLU(G) * E[ids]; is_bf16 selects the element type of G, E, H
 hipError_t stem_silu_gather(stem_ctx* ctx, int is_bf16, const void* G, const int32_t* ids, const void* E,
                             int E_rows, void* H, int64_t T, int F, hipStream_t s);
