@@ -32,7 +32,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -86,6 +88,12 @@ def main() -> int:
         L.stem_embed_grad(ctx, inp["ids"], dU, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, dE_rows)
         L.stem_embed_sparse_adamw(ctx, uniq_ids, n_uniq, dE_rows, E, master, m, v, step=step_no[0], **hp)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -127,6 +135,12 @@ def main() -> int:
             k["gbs"] = round(algo_bytes[name] / (avg * 1e-3) / 1e9, 1)
             k["frac_hbm_peak"] = round(k["gbs"] / PEAK_HBM_GBS, 4)
         kernels[name] = k
+    # measured HBM-side bytes per launch (rocprofv3 FETCH_SIZE / WRITE_SIZE), if a summary for this workload is committed
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % shape.name.replace("-", "_"))
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = {k: v for k, v in json.load(fh).items() if not k.startswith("_")}
     gemms = {k: v for k, v in kernels.items() if k.startswith("gemm_")}
     dom = max(gemms, key=lambda k: gemms[k]["avg_ms"] * gemms[k]["launches"])
     all_gemm_ms = sum(v["avg_ms"] for v in gemms.values())
@@ -137,7 +151,7 @@ def main() -> int:
         "peak": peak_tf,
         "unit": "TFLOP/s",
         "frac": round(gemms[dom]["tflops"] / peak_tf, 4),
-        "traffic": None,
+        "traffic": traffic.get(dom),
         "all_gemms_tflops": round(len(gemms) * gemm_flop / (all_gemm_ms * 1e-3) / 1e12, 2),
         "all_gemms_frac": round(len(gemms) * gemm_flop / (all_gemm_ms * 1e-3) / 1e12 / peak_tf, 4),
     }

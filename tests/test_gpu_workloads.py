@@ -1,0 +1,220 @@
+"""GPU parity at the full workload sizes (sampled outputs the oracle can compute one by one),
+the stacked decode chain, and the host-resident-table mode.  All through the C ABI."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import stem_oracle as O
+from paper_2601_10639_amd import inputs, stemlib as L
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _rows(t, idx):
+    """Rows idx of a device tensor as fp64 numpy."""
+    return inputs.to_f64(t[torch.as_tensor(np.asarray(idx, dtype=np.int64), device=t.device)])
+
+
+def _full_size_case(name, seed):
+    """Whole hot path in the launch configuration bench.py times; the oracle is evaluated
+    (a) on sampled tokens with all features: y, G, H, dx, dU rows;
+    (b) on sampled features with all tokens: columns of dW_down, rows of dW_gate, columns of the
+        table gradient and of the AdamW state.  Both are exact restrictions of the layer."""
+    shape = inputs.SHAPES[name]
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    tol = Hn.TOL[shape.dtype]
+    inp = inputs.layer_inputs(shape, seed, device=DEV)
+    ctx = Hn.make_ctx(shape, T)
+    out = Hn.hip_forward_backward(ctx, inp)
+    eg = Hn.hip_embed_grad(ctx, inp["ids"], out["dU"], V)
+    L.stem_sync_status(ctx)
+    ids = inp["ids"].cpu().numpy()
+    U = Hn.check_integers(eg, ids)
+
+    rng = np.random.default_rng(seed)
+    # (a) token sample: first, last, tile borders, random
+    tok = np.unique(np.concatenate([[0, 1, 255, 256, 257, T - 257, T - 256, T - 1], rng.integers(0, T, 40)]))
+    uniq_t, remap_t = np.unique(ids[tok], return_inverse=True)
+    E_t = _rows(inp["E"], uniq_t)
+    Wg, Wd = inputs.to_f64(inp["W_gate"]), inputs.to_f64(inp["W_down"])
+    x_t, dy_t = _rows(inp["x"], tok), _rows(inp["dy"], tok)
+    y, fw = O.ffn_forward(x_t, remap_t, Wg, Wd, E_t)
+    bw = O.ffn_backward(dy_t, x_t, remap_t, Wg, Wd, E_t)
+    errs = {
+        "y": Hn.max_rel(_rows(out["y"], tok), y), "G": Hn.max_rel(_rows(out["G"], tok), fw["g"]),
+        "H": Hn.max_rel(_rows(out["H"], tok), fw["h"]), "dx": Hn.max_rel(_rows(out["dx"], tok), bw["dx"]),
+        "dU": Hn.max_rel(_rows(out["dU"], tok), bw["dU"]),
+    }
+    # (b) feature sample, all tokens
+    fs = np.unique(np.concatenate([[0, 1, 255, 256, F - 1], rng.integers(0, F, 27)]))
+    fs_t = torch.as_tensor(fs, device=DEV)
+    uniq_all, remap_all = np.unique(ids, return_inverse=True)
+    E_f = inputs.to_f64(inp["E"][torch.as_tensor(uniq_all.astype(np.int64), device=DEV)][:, fs_t])
+    x_all, dy_all = inputs.to_f64(inp["x"]), inputs.to_f64(inp["dy"])
+    bwf = O.ffn_backward(dy_all, x_all, remap_all, Wg[fs], Wd[:, fs], E_f)
+    errs["dW_gate"] = Hn.max_rel(inputs.to_f64(out["dW_gate"][fs_t]), bwf["dW_gate"])
+    errs["dW_down"] = Hn.max_rel(inputs.to_f64(out["dW_down"][:, fs_t]), bwf["dW_down"])
+    oeg = O.embed_grad(ids, bwf["dU"])
+    np.testing.assert_array_equal(oeg["uniq_ids"], uniq_all)
+    errs["dE_rows"] = Hn.max_rel(inputs.to_f64(eg["dE_rows"][:U][:, fs_t]), oeg["dE_rows"])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, f"{name}: over tolerance {tol}: {bad} (all: {errs})"
+    print(name, "max-relative errors", {k: float("%.3g" % v) for k, v in errs.items()}, "n_uniq", U)
+
+    # sparse AdamW on the touched rows (own gradients on each side; see the small-size test for why
+    # parameters are compared where the gradient's sign is certain)
+    E = inp["E"]
+    E0_rows = _rows(E, uniq_all)[:, fs]
+    master = E.float()
+    m = torch.zeros(V, F, dtype=torch.float32, device=DEV)
+    v = torch.zeros(V, F, dtype=torch.float32, device=DEV)
+    L.stem_embed_sparse_adamw(ctx, eg["uniq_ids"], eg["n_uniq"], eg["dE_rows"], E, master, m, v, step=1, **Hn.ADAMW)
+    L.stem_sync_status(ctx)
+    ui = torch.as_tensor(uniq_all.astype(np.int64), device=DEV)
+    z = np.zeros_like(E0_rows)
+    p_ref, m_ref, v_ref = O.sparse_adamw_rows(oeg["dE_rows"], E0_rows, z, z, step=1, **Hn.ADAMW)
+    assert Hn.max_rel(inputs.to_f64(m[ui][:, fs_t]), m_ref) <= tol
+    assert Hn.max_rel(inputs.to_f64(v[ui][:, fs_t]), v_ref) <= 2 * tol
+    sure = np.abs(oeg["dE_rows"]) > 2 * tol * np.abs(oeg["dE_rows"]).max()
+    p_gpu = inputs.to_f64(master[ui][:, fs_t])
+    assert np.abs(p_gpu - p_ref)[sure].max() / np.abs(p_ref).max() <= 1e-5
+    np.testing.assert_array_equal(inputs.to_f64(E[ui][:, fs_t]), O.bf16_round(p_gpu))
+    # an untouched row keeps its bits
+    untouched = int(np.setdiff1d(np.arange(min(V, 4 * T)), uniq_all)[0])
+    assert not m[untouched].any() and not v[untouched].any()
+    ctx.close()
+
+
+def test_c2_350m_shaped_layer_full_size():
+    _full_size_case("C2", seed=21)
+
+
+def test_c3_1b_shaped_layer_full_size():
+    _full_size_case("C3", seed=22)
+
+
+def test_c4_decode_chain_sixteen_layers():
+    """256 single tokens through 16 stacked 1B-shaped layers, residual stream rounded to bf16 between
+    layers on both sides; every layer has its own weights and table, the ids are the same."""
+    shape = inputs.SHAPES["C4"]
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    n_layers = 16
+    ids_np = inputs.zipf_ids(T, V, seed=31)
+    ids = torch.from_numpy(ids_np).to(DEV)
+    uniq, remap = np.unique(ids_np, return_inverse=True)
+    ui = torch.as_tensor(uniq.astype(np.int64), device=DEV)
+    ctx = Hn.make_ctx(shape, T)
+    x0 = inputs.normal((T, d), 1.0, 32, torch.bfloat16, DEV)
+    x = x0.clone()
+    y = torch.empty_like(x)
+    layers_ref, outs = [], []
+    for l in range(n_layers):
+        Wg = inputs.normal((F, d), 0.02, 100 + 3 * l, torch.bfloat16, DEV)
+        Wd = inputs.normal((d, F), 0.02, 101 + 3 * l, torch.bfloat16, DEV)
+        E = inputs.normal((V, F), 0.02, 102 + 3 * l, torch.bfloat16, DEV)
+        L.stem_ffn_forward(ctx, x, ids, Wg, Wd, E, y)
+        x = (x.float() + y.float()).to(torch.bfloat16)
+        outs.append(x.float().cpu().numpy().astype(np.float64))
+        layers_ref.append((inputs.to_f64(Wg), inputs.to_f64(Wd), inputs.to_f64(E[ui])))
+        del E
+    L.stem_sync_status(ctx)
+    ref = O.decode_chain(inputs.to_f64(x0), remap, layers_ref)
+    worst = max(Hn.max_rel(outs[l], ref[l]) for l in range(n_layers))
+    assert worst <= Hn.TOL["bf16"], worst
+    print("decode chain: worst layer error", worst)
+    ctx.close()
+
+
+def _prefetch_case(shape, T, ids_np, seed, mode=None):
+    d, F, V = shape.d_model, shape.d_ff, shape.vocab
+    dt = inputs.torch_dtype(shape.dtype)
+    ctx = Hn.make_ctx(shape, T)
+    E_host = inputs.normal((V, F), 0.02, seed, dt, "cpu").pin_memory()
+    ids_host = torch.from_numpy(ids_np)
+    o_uniq, o_remap = O.dedup_remap(ids_np)
+    cap = len(o_uniq) + 3
+    E_compact = torch.full((cap, F), 7.0, dtype=dt, device=DEV)
+    remap = torch.empty(T, dtype=torch.int32, device=DEV)
+    uniq_host = torch.empty(cap, dtype=torch.int32)
+    old = os.environ.pop("STEM_PREFETCH_MODE", None)
+    if mode:
+        os.environ["STEM_PREFETCH_MODE"] = mode
+    try:
+        n, ev = L.stem_prefetch_rows(ctx, E_host, ids_host, E_compact, remap, uniq_host)
+    finally:
+        os.environ.pop("STEM_PREFETCH_MODE", None)
+        if old is not None:
+            os.environ["STEM_PREFETCH_MODE"] = old
+    assert n == len(o_uniq) and ev
+    x = inputs.normal((T, d), 1.0, seed + 1, dt, DEV)
+    Wg = inputs.normal((F, d), 0.02, seed + 2, dt, DEV)
+    Wd = inputs.normal((d, F), 0.02, seed + 3, dt, DEV)
+    y = torch.empty(T, d, dtype=dt, device=DEV)
+    L.stem_ffn_forward(ctx, x, remap, Wg, Wd, E_compact, y, wait_event=ev, E_rows=n)
+    L.stem_sync_status(ctx)
+    # integers and copied rows: bit-exact
+    np.testing.assert_array_equal(uniq_host[:n].numpy(), o_uniq)
+    np.testing.assert_array_equal(remap.cpu().numpy(), o_remap)
+    want_rows = E_host[torch.from_numpy(o_uniq.astype(np.int64))]
+    assert torch.equal(E_compact[:n].cpu().view(torch.int16 if dt == torch.bfloat16 else torch.int32),
+                       want_rows.view(torch.int16 if dt == torch.bfloat16 else torch.int32))
+    assert bool((E_compact[n:] == 7.0).all())
+    # same kernels on the device-resident table with the original ids: bit-identical output
+    E_dev = E_host.to(DEV)
+    y2 = torch.empty_like(y)
+    L.stem_ffn_forward(ctx, x, ids_host.to(DEV), Wg, Wd, E_dev, y2, wait_event=ev)
+    L.stem_sync_status(ctx)
+    assert torch.equal(y, y2)
+    ctx.close()
+    return x, Wg, Wd, E_host, y, n
+
+
+@pytest.mark.parametrize("dtype,mode", [("bf16", None), ("bf16", "memcpy"), ("f32", None)])
+def test_prefetch_rows_small(dtype, mode):
+    shape = inputs.StemShape("host-small", 128, 256, 5000, 1, 3000, dtype)
+    ids_np = inputs.zipf_ids(3000, 5000, seed=41)
+    x, Wg, Wd, E_host, y, n = _prefetch_case(shape, 3000, ids_np, seed=42, mode=mode)
+    ref, _ = O.ffn_forward(inputs.to_f64(x), ids_np, inputs.to_f64(Wg), inputs.to_f64(Wd), inputs.to_f64(E_host))
+    assert Hn.max_rel(y.float().cpu(), ref) <= Hn.TOL[dtype]
+
+
+def test_prefetch_rows_errors():
+    shape = inputs.StemShape("host-err", 64, 64, 100, 1, 50, "bf16")
+    ctx = Hn.make_ctx(shape, 50)
+    E_host = inputs.normal((100, 64), 0.02, 1, torch.bfloat16, "cpu").pin_memory()
+    ids = torch.arange(50, dtype=torch.int32)
+    E_compact = torch.empty(10, 64, dtype=torch.bfloat16, device=DEV)
+    remap = torch.empty(50, dtype=torch.int32, device=DEV)
+    with pytest.raises(L.StemError) as e:
+        L.stem_prefetch_rows(ctx, E_host, ids, E_compact, remap)
+    assert e.value.status == L.STEM_ERR_WORKSPACE
+    bad = ids.clone(); bad[7] = 100
+    E_big = torch.empty(50, 64, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(L.StemError) as e:
+        L.stem_prefetch_rows(ctx, E_host, bad, E_big, remap)
+    assert e.value.status == L.STEM_ERR_ID_RANGE
+    n, ev = L.stem_prefetch_rows(ctx, E_host, ids, E_big, remap)   # the context is still usable
+    assert n == 50
+    torch.cuda.synchronize()
+    ctx.close()
+
+
+@pytest.mark.parametrize("dist", ["zipf", "uniform"])
+def test_c5_long_context_host_resident_table(dist):
+    """One 1B-shaped layer, 65536 tokens, table in pinned host memory; the oracle checks sampled tokens."""
+    shape = inputs.SHAPES["C5"]
+    T, V = shape.tokens, shape.vocab
+    ids_np = inputs.zipf_ids(T, V, seed=51) if dist == "zipf" else inputs.uniform_ids(T, V, seed=52)
+    x, Wg, Wd, E_host, y, n = _prefetch_case(shape, T, ids_np, seed=53)
+    rng = np.random.default_rng(5)
+    tok = np.unique(np.concatenate([[0, 255, 256, T - 1], rng.integers(0, T, 28)]))
+    uniq_t, remap_t = np.unique(ids_np[tok], return_inverse=True)
+    E_t = inputs.to_f64(E_host[torch.from_numpy(uniq_t.astype(np.int64))])
+    ref, _ = O.ffn_forward(_rows(x, tok), remap_t, inputs.to_f64(Wg), inputs.to_f64(Wd), E_t)
+    err = Hn.max_rel(_rows(y, tok), ref)
+    assert err <= Hn.TOL["bf16"], err
+    print(f"C5 {dist}: n_uniq {n} ({n * shape.d_ff * 2 / 1e6:.0f} MB of rows), sampled error {err:.3g}")
