@@ -9,6 +9,7 @@ struct AdamConsts {
 };
 
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // Workgroups stride over the touched rows; threads stride over the row in float4 steps.
 template <bool BF16>
@@ -28,15 +29,16 @@ __global__ __launch_bounds__(256) void adamw_kernel(const int32_t* __restrict__ 
     const size_t ro = (size_t)r * F;
     const float* gr = g + (size_t)j * F;
     float* pr = master ? master + ro : reinterpret_cast<float*>(E) + ro;
+#pragma unroll 2
     for (int c = threadIdx.x * 4; c < F; c += 256 * 4) {
-      const float4 g4 = *reinterpret_cast<const float4*>(gr + c);
-      const float4 p4 = *reinterpret_cast<const float4*>(pr + c);
-      const float4 m4 = *reinterpret_cast<const float4*>(m + ro + c);
-      const float4 v4 = *reinterpret_cast<const float4*>(v + ro + c);
-      const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
-      float pp[4] = {p4.x, p4.y, p4.z, p4.w};
-      float mm[4] = {m4.x, m4.y, m4.z, m4.w};
-      float vv[4] = {v4.x, v4.y, v4.z, v4.w};
+      const f32x4_t g4 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(gr + c));
+      const f32x4_t p4 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(pr + c));
+      const f32x4_t m4 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(m + ro + c));
+      const f32x4_t v4 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(v + ro + c));
+      const float gg[4] = {g4[0], g4[1], g4[2], g4[3]};
+      float pp[4] = {p4[0], p4[1], p4[2], p4[3]};
+      float mm[4] = {m4[0], m4[1], m4[2], m4[3]};
+      float vv[4] = {v4[0], v4[1], v4[2], v4[3]};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         mm[q] = k.b1 * mm[q] + (1.0f - k.b1) * gg[q];
@@ -45,9 +47,10 @@ __global__ __launch_bounds__(256) void adamw_kernel(const int32_t* __restrict__ 
         const float vhat = vv[q] * k.inv_c2;
         pp[q] = pp[q] - k.lr * k.wd * pp[q] - k.lr * mhat / (sqrtf(vhat) + k.eps);
       }
-      *reinterpret_cast<float4*>(pr + c) = make_float4(pp[0], pp[1], pp[2], pp[3]);
-      *reinterpret_cast<float4*>(m + ro + c) = make_float4(mm[0], mm[1], mm[2], mm[3]);
-      *reinterpret_cast<float4*>(v + ro + c) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+      const f32x4_t po = {pp[0], pp[1], pp[2], pp[3]}, mo = {mm[0], mm[1], mm[2], mm[3]}, vo = {vv[0], vv[1], vv[2], vv[3]};
+      __builtin_nontemporal_store(po, reinterpret_cast<f32x4_t*>(pr + c));
+      __builtin_nontemporal_store(mo, reinterpret_cast<f32x4_t*>(m + ro + c));
+      __builtin_nontemporal_store(vo, reinterpret_cast<f32x4_t*>(v + ro + c));
       if (BF16) {
         bf16x4_t o;
         o[0] = (__bf16)pp[0]; o[1] = (__bf16)pp[1]; o[2] = (__bf16)pp[2]; o[3] = (__bf16)pp[3];

@@ -179,27 +179,171 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* __restrict_
   }
 }
 
+
+// ---- one-workgroup path: sort, unique and run index in a single launch ---------------
+// When bits(V-1) + bits(T-1) <= 32 the pair (id, position) packs into one 32-bit key, so
+// two 64 KB LDS buffers hold the whole problem (T <= 16384).  The passes run over the id
+// bits only; the position bits ride along and make the order total.
+constexpr int FUSED_MAX_T = 16384;
+
+__global__ __launch_bounds__(1024) void sort_unique_fused_kernel(const int32_t* __restrict__ ids, int T, int V,
+                                                                 int pos_bits, int passes,
+                                                                 int32_t* __restrict__ sorted_ids,
+                                                                 int32_t* __restrict__ perm,
+                                                                 int32_t* __restrict__ uniq_ids,
+                                                                 int32_t* __restrict__ seg_offsets,
+                                                                 int32_t* __restrict__ n_uniq,
+                                                                 int32_t* __restrict__ seg_of, int32_t* flag) {
+  __shared__ uint32_t buf[2][FUSED_MAX_T];
+  __shared__ int table[RADIX * SORT_WAVES];  // [digit][wave], scanned in place
+  __shared__ int wsum[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per_wave = (T + SORT_WAVES - 1) / SORT_WAVES;      // contiguous keys per wavefront
+  const int w0 = wave * per_wave, w1 = min(T, w0 + per_wave);
+  const uint32_t pos_mask = (1u << pos_bits) - 1u;
+  constexpr int ITEMS = FUSED_MAX_T / 1024;
+  {
+    int kv[ITEMS];
+#pragma unroll
+    for (int u = 0; u < ITEMS; ++u) kv[u] = (tid + 1024 * u) < T ? ids[tid + 1024 * u] : 0;
+    bool bad = false;
+#pragma unroll
+    for (int u = 0; u < ITEMS; ++u) {
+      const int i = tid + 1024 * u;
+      int k = kv[u];
+      if ((unsigned)k >= (unsigned)V) { bad = true; k = k < 0 ? 0 : V - 1; }
+      if (i < T) buf[0][i] = ((uint32_t)k << pos_bits) | (uint32_t)i;
+    }
+    if (bad) *flag = 1;
+  }
+  __syncthreads();
+  const uint64_t below = (1ull << lane) - 1ull;
+  int cur = 0;
+  for (int p = 0; p < passes; ++p) {
+    const int shift = pos_bits + p * RADIX_BITS;
+    table[tid] = 0;
+    __syncthreads();
+    for (int i = w0 + lane; i < w1; i += 64) atomicAdd(&table[((buf[cur][i] >> shift) & (RADIX - 1)) * SORT_WAVES + wave], 1);
+    __syncthreads();
+    {  // exclusive scan of the 1024 table entries, one per thread
+      const int v = table[tid];
+      int inc = v;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+      }
+      if (lane == 63) wsum[wave] = inc;
+      __syncthreads();
+      if (tid == 0) {
+        int c = 0;
+        for (int w = 0; w < 16; ++w) { const int t = wsum[w]; wsum[w] = c; c += t; }
+      }
+      __syncthreads();
+      table[tid] = wsum[wave] + inc - v;
+    }
+    __syncthreads();
+    for (int i0 = w0; i0 < w1; i0 += 64) {
+      const int i = i0 + lane;
+      const bool valid = i < w1;
+      uint32_t key = 0;
+      int d = 0;
+      if (valid) { key = buf[cur][i]; d = (key >> shift) & (RADIX - 1); }
+      uint64_t same = __ballot(valid);
+#pragma unroll
+      for (int b = 0; b < RADIX_BITS; ++b) {
+        const bool bit = (d >> b) & 1;
+        const uint64_t bb = __ballot(valid && bit);
+        same &= bit ? bb : ~bb;
+      }
+      int pos = 0;
+      if (valid) pos = table[d * SORT_WAVES + wave] + __popcll(same & below);
+      __builtin_amdgcn_wave_barrier();
+      if (valid && (same & below) == 0) table[d * SORT_WAVES + wave] += __popcll(same);
+      __builtin_amdgcn_wave_barrier();
+      if (valid) buf[cur ^ 1][pos] = key;
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+  // unpack (coalesced), head flags into the free buffer
+  uint32_t* aux = buf[cur ^ 1];
+#pragma unroll
+  for (int u = 0; u < ITEMS; ++u) {
+    const int k = tid + 1024 * u;
+    if (k < T) {
+      const uint32_t key = buf[cur][k];
+      const int id = (int)(key >> pos_bits);
+      sorted_ids[k] = id;
+      perm[k] = (int)(key & pos_mask);
+      aux[k] = (k == 0 || id != (int)(buf[cur][k - 1] >> pos_bits)) ? 1u : 0u;
+    }
+  }
+  __syncthreads();
+  // run numbering in key order: each thread owns ITEMS consecutive positions
+  const int b0 = tid * ITEMS;
+  int heads = 0;
+#pragma unroll
+  for (int u = 0; u < ITEMS; ++u) if (b0 + u < T) heads += (int)aux[b0 + u];
+  int inc = heads;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  if (tid == 0) {
+    int c = 0;
+    for (int w = 0; w < 16; ++w) { const int t = wsum[w]; wsum[w] = c; c += t; }
+    seg_offsets[c] = T;
+    *n_uniq = c;
+  }
+  __syncthreads();
+  int run = wsum[wave] + inc - heads;
+#pragma unroll
+  for (int u = 0; u < ITEMS; ++u) {
+    const int k = b0 + u;
+    if (k < T) {
+      if (aux[k]) { uniq_ids[run] = (int)(buf[cur][k] >> pos_bits); seg_offsets[run] = k; ++run; }
+      aux[k] = (uint32_t)(run - 1);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < ITEMS; ++u) {
+    const int k = tid + 1024 * u;
+    if (k < T) seg_of[k] = (int)aux[k];
+  }
+}
+
 // ---- segmented sum -----------------------------------------------------------------
 constexpr int SEG_ROWS = 32;  // sorted positions per chunk
 
 template <bool BF16> struct RowVec;
 template <> struct RowVec<true> {
   static constexpr int COLS = 8;
-  static __device__ __forceinline__ void load(const void* base, int64_t row, int F, int col, float (&f)[8]) {
-    const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(base) + row * F + col);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  typedef __attribute__((ext_vector_type(4))) uint32_t raw_t;
+  static __device__ __forceinline__ raw_t load(const void* base, int64_t row, int F, int col) {
+    return __builtin_nontemporal_load(reinterpret_cast<const raw_t*>(reinterpret_cast<const bf16_t*>(base) + row * F + col));
+  }
+  static __device__ __forceinline__ void add(const raw_t& v, float (&acc)[8]) {
+    const uint32_t w[4] = {v[0], v[1], v[2], v[3]};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      f[2 * q] = __uint_as_float(w[q] << 16);
-      f[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+      acc[2 * q] += __uint_as_float(w[q] << 16);
+      acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
     }
   }
 };
 template <> struct RowVec<false> {
   static constexpr int COLS = 4;
-  static __device__ __forceinline__ void load(const void* base, int64_t row, int F, int col, float (&f)[4]) {
-    const float4 v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + row * F + col);
-    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  typedef float4 raw_t;
+  static __device__ __forceinline__ raw_t load(const void* base, int64_t row, int F, int col) {
+    return *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + row * F + col);
+  }
+  static __device__ __forceinline__ void add(const raw_t& v, float (&acc)[4]) {
+    acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
   }
 };
 
@@ -213,57 +357,63 @@ __device__ __forceinline__ void store_cols(float* dst, const float (&a)[COLS]) {
 // of 256*COLS columns, in ascending position.  A run that lies wholly inside the chunk
 // is written to its output row; the (at most two) pieces of runs that cross the chunk's
 // borders go to part[c][0] (piece holding the chunk's first position) or part[c][1].
+// The chunk's row numbers and run indices are fetched once into LDS, so all row loads can
+// be in flight together and run ends need no further global reads.
 template <bool BF16>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(const void* __restrict__ dU,
                                                          const int32_t* __restrict__ perm,
-                                                         const int32_t* __restrict__ seg_of,
-                                                         const int32_t* __restrict__ seg_offsets, int64_t T,
-                                                         int F, float* __restrict__ dE_rows,
+                                                         const int32_t* __restrict__ seg_of, int64_t T, int F,
+                                                         float* __restrict__ dE_rows,
                                                          float* __restrict__ part) {
   constexpr int COLS = RowVec<BF16>::COLS;
-  const int c = blockIdx.x;
+  __shared__ int s_perm[SEG_ROWS];
+  __shared__ int s_seg[SEG_ROWS + 2];  // [0] = run of the position before the chunk, [n+1] = of the one after
+  const int c = blockIdx.y;
   const int k0 = c * SEG_ROWS;
   const int k1 = (int)min((int64_t)k0 + SEG_ROWS, T);
-  const int col = (blockIdx.y * 256 + threadIdx.x) * COLS;
+  const int n = k1 - k0;
+  const int tid = threadIdx.x;
+  if (tid < n) s_perm[tid] = perm[k0 + tid];
+  if (tid < n + 2) {
+    const int64_t k = (int64_t)k0 - 1 + tid;
+    s_seg[tid] = (k >= 0 && k < T) ? seg_of[k] : -1;
+  }
+  __syncthreads();
+  const int col = (blockIdx.x * 256 + tid) * COLS;
   if (col >= F) return;
-  const int first_seg = seg_of[k0];
+  const int first_seg = s_seg[1], last_seg = s_seg[n];
+  const bool first_open = s_seg[0] == first_seg;      // the first run began before the chunk
+  const bool last_open = s_seg[n + 1] == last_seg;    // the last run goes on after the chunk
   float acc[COLS];
 #pragma unroll
   for (int q = 0; q < COLS; ++q) acc[q] = 0.f;
   int cur = first_seg;
 
   auto flush = [&](int j) {
-    const int lo = seg_offsets[j], hi = seg_offsets[j + 1];
-    float* dst;
-    if (lo >= k0 && hi <= k1) dst = dE_rows + (int64_t)j * F + col;
-    else dst = part + ((int64_t)c * 2 + (j == first_seg ? 0 : 1)) * F + col;
+    const bool open = (j == first_seg && first_open) || (j == last_seg && last_open);
+    float* dst = open ? part + ((int64_t)c * 2 + (j == first_seg ? 0 : 1)) * F + col
+                      : dE_rows + (int64_t)j * F + col;
     store_cols<COLS>(dst, acc);
   };
 
-  constexpr int UNR = 8;
-  for (int kb = k0; kb < k1; kb += UNR) {
-    float data[UNR][COLS];
-    int segs[UNR];
+  constexpr int UNR = 16;
+#pragma unroll
+  for (int kb = 0; kb < SEG_ROWS; kb += UNR) {
+    typename RowVec<BF16>::raw_t data[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (kb + u < n) data[u] = RowVec<BF16>::load(dU, s_perm[kb + u], F, col);
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-      const int k = kb + u;
-      if (k < k1) {
-        segs[u] = seg_of[k];
-        RowVec<BF16>::load(dU, perm[k], F, col, data[u]);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      const int k = kb + u;
-      if (k < k1) {
-        if (segs[u] != cur) {
+      if (kb + u < n) {
+        const int sg = s_seg[kb + u + 1];
+        if (sg != cur) {
           flush(cur);
-          cur = segs[u];
+          cur = sg;
 #pragma unroll
           for (int q = 0; q < COLS; ++q) acc[q] = 0.f;
         }
-#pragma unroll
-        for (int q = 0; q < COLS; ++q) acc[q] += data[u][q];
+        RowVec<BF16>::add(data[u], acc);
       }
     }
   }
@@ -278,13 +428,16 @@ __global__ __launch_bounds__(256) void seg_combine_kernel(const int32_t* __restr
                                                           const float* __restrict__ part) {
   const int c = blockIdx.x;
   const int k0 = c * SEG_ROWS;
-  const int k1 = (int)min((int64_t)k0 + SEG_ROWS, T);
+  const int64_t k1 = (int64_t)k0 + SEG_ROWS;
+  if (k1 >= T) return;                                 // nothing after this chunk
   const int j = seg_of[k1 - 1];
-  const int lo = seg_offsets[j], hi = seg_offsets[j + 1];
-  if (!(lo >= k0 && hi > k1)) return;
+  if (seg_of[k1] != j) return;                         // the last run ends with the chunk
+  const int first = seg_of[k0];
+  if (first == j && k0 > 0 && seg_of[k0 - 1] == j) return;  // the run began in an earlier chunk
   const int col = (blockIdx.y * 256 + threadIdx.x) * COLS;
   if (col >= F) return;
-  const int slot = (seg_of[k0] == j) ? 0 : 1;
+  const int slot = (first == j) ? 0 : 1;
+  const int hi = seg_offsets[j + 1];
   const int ce = (hi - 1) / SEG_ROWS;
   float acc[COLS];
   {
@@ -292,7 +445,7 @@ __global__ __launch_bounds__(256) void seg_combine_kernel(const int32_t* __restr
 #pragma unroll
     for (int q = 0; q < COLS; ++q) acc[q] = src[q];
   }
-  constexpr int UNR = 8;
+  constexpr int UNR = 16;
   for (int cb = c + 1; cb <= ce; cb += UNR) {
     float data[UNR][COLS];
 #pragma unroll
@@ -332,9 +485,16 @@ int64_t stem_sort_count_entries(int64_t max_tokens) {
 hipError_t stem_sort_unique(stem_ctx* ctx, const int32_t* ids, int64_t T, int V, int32_t* sorted_ids,
                             int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets, int32_t* n_uniq,
                             hipStream_t s) {
+  const int passes = (bits_for(V) + RADIX_BITS - 1) / RADIX_BITS;
+  const int pos_bits = bits_for((int)T);
+  if (T <= FUSED_MAX_T && bits_for(V) + pos_bits <= 32) {
+    ProfScope ps(ctx, K_SORT_FUSED, s);
+    hipLaunchKernelGGL(sort_unique_fused_kernel, dim3(1), dim3(1024), 0, s, ids, (int)T, V, pos_bits, passes,
+                       sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, ctx->seg_of, ctx->flag);
+    return hipGetLastError();
+  }
   const int tiles = (int)((T + SORT_TILE - 1) / SORT_TILE);
   const int nW = tiles * SORT_WAVES;
-  const int passes = (bits_for(V) + RADIX_BITS - 1) / RADIX_BITS;
   const int32_t* src_k = ids;
   const int32_t* src_v = nullptr;
   for (int p = 0; p < passes; ++p) {
@@ -374,11 +534,11 @@ hipError_t stem_seg_reduce(stem_ctx* ctx, int is_bf16, const void* dU, const int
   {
     ProfScope ps(ctx, K_SEG_REDUCE, s);
     if (is_bf16)
-      hipLaunchKernelGGL(seg_reduce_kernel<true>, dim3(chunks, slabs), dim3(256), 0, s, dU, perm, ctx->seg_of,
-                         seg_offsets, T, F, dE_rows, ctx->seg_part);
+      hipLaunchKernelGGL(seg_reduce_kernel<true>, dim3(slabs, chunks), dim3(256), 0, s, dU, perm, ctx->seg_of, T, F,
+                         dE_rows, ctx->seg_part);
     else
-      hipLaunchKernelGGL(seg_reduce_kernel<false>, dim3(chunks, slabs), dim3(256), 0, s, dU, perm, ctx->seg_of,
-                         seg_offsets, T, F, dE_rows, ctx->seg_part);
+      hipLaunchKernelGGL(seg_reduce_kernel<false>, dim3(slabs, chunks), dim3(256), 0, s, dU, perm, ctx->seg_of, T,
+                         F, dE_rows, ctx->seg_part);
   }
   {
     ProfScope ps(ctx, K_SEG_COMBINE, s);

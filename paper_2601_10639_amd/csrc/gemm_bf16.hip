@@ -51,15 +51,21 @@ __device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
 }
 
 // A buffer resource that moves along the operand: base advances, the record count shrinks.
+// The descriptor is rebuilt once per K tile (a handful of scalar instructions), not per load.
 struct Window {
   const char* base;
-  int64_t left;  // bytes from base to the end of the operand (may go negative)
-  __device__ __forceinline__ rsrc_t rsrc() const {
-    const int64_t l = left < 0 ? 0 : left;
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, (int)(l > 0x7fffffff ? 0x7fffffff : l),
-                                             0x00020000);
+  int left;  // bytes from base to the end of the operand (operands stay below 2 GiB; may go negative)
+  rsrc_t r;
+  __device__ __forceinline__ void set(const void* p, int64_t bytes) {
+    base = reinterpret_cast<const char*>(p);
+    left = (int)bytes;
+    rebuild();
   }
-  __device__ __forceinline__ void advance(int64_t bytes) { base += bytes; left -= bytes; }
+  __device__ __forceinline__ void rebuild() {
+    r = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, left < 0 ? 0 : left, 0x00020000);
+  }
+  __device__ __forceinline__ rsrc_t rsrc() const { return r; }
+  __device__ __forceinline__ void advance(int bytes) { base += bytes; left -= bytes; rebuild(); }
 };
 
 // ---- KC operand: global -> LDS direct -----------------------------------------------
@@ -69,8 +75,7 @@ struct LoaderKC {
   uint32_t off[8];
   Window win;
   __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int row0, int wave, int lane) {
-    win.base = reinterpret_cast<const char*>(p);
-    win.left = (int64_t)rows * ld * 2;
+    win.set(p, (int64_t)rows * ld * 2);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = (wave * 8 + i) * 8 + (lane >> 3);
@@ -94,8 +99,7 @@ struct LoaderMC {
   Window win;
   uint4 st[8];
   __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int K, int row0, int tid) {
-    win.base = reinterpret_cast<const char*>(p);
-    win.left = (int64_t)K * ld * 2;
+    win.set(p, (int64_t)K * ld * 2);
     ld2 = (uint32_t)ld * 2;
     const int kb = tid & 7, rb = tid >> 3;
     off0 = (row0 + rb * 8) < rows ? (uint32_t)(((int64_t)kb * 8 * ld + row0 + rb * 8) * 2) : OOB;
@@ -104,7 +108,7 @@ struct LoaderMC {
     const uint32_t o = off0 == OOB ? OOB : off0 + kk * ld2;
     st[kk] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(win.rsrc(), o, 0, 0));
   }
-  __device__ __forceinline__ void next_tile() { win.advance((int64_t)BK * ld2); }
+  __device__ __forceinline__ void next_tile() { win.advance((int)(BK * ld2)); }
   static __device__ __forceinline__ uint32_t pick(const uint4& v, int q) {
     return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
   }
