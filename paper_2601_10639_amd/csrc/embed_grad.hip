@@ -196,6 +196,7 @@ __global__ __launch_bounds__(1024) void sort_unique_fused_kernel(const int32_t* 
                                                                  int32_t* __restrict__ seg_of, int32_t* flag) {
   __shared__ uint32_t buf[2][FUSED_MAX_T];
   __shared__ int table[RADIX * SORT_WAVES];  // [digit][wave], scanned in place
+  __shared__ __attribute__((aligned(16))) uint8_t cnt8[SORT_WAVES][RADIX][16];
   __shared__ int wsum[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per_wave = (T + SORT_WAVES - 1) / SORT_WAVES;      // contiguous keys per wavefront
@@ -219,11 +220,46 @@ __global__ __launch_bounds__(1024) void sort_unique_fused_kernel(const int32_t* 
   __syncthreads();
   const uint64_t below = (1ull << lane) - 1ull;
   int cur = 0;
+  // Per pass and wavefront: 16 rounds of 64 keys.  A key's rank among equal digits of its round
+  // comes from ballots; the per-round digit counts go to cnt8[wave][digit][round] (bytes), lane d
+  // then turns digit d's 16 counts into running offsets, so no round waits for the one before.
   for (int p = 0; p < passes; ++p) {
     const int shift = pos_bits + p * RADIX_BITS;
-    table[tid] = 0;
-    __syncthreads();
-    for (int i = w0 + lane; i < w1; i += 64) atomicAdd(&table[((buf[cur][i] >> shift) & (RADIX - 1)) * SORT_WAVES + wave], 1);
+    uint32_t key[ITEMS];
+    uint32_t dr[ITEMS];  // digit | rank << 8 | valid << 16
+#pragma unroll
+    for (int r = 0; r < ITEMS; ++r) {
+      const int i = w0 + r * 64 + lane;
+      key[r] = i < w1 ? buf[cur][i] : 0u;
+    }
+    *reinterpret_cast<uint4*>(&cnt8[wave][lane][0]) = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < ITEMS; ++r) {
+      const bool valid = (w0 + r * 64 + lane) < w1;
+      const int d = (key[r] >> shift) & (RADIX - 1);
+      uint64_t same = __ballot(valid);
+#pragma unroll
+      for (int b = 0; b < RADIX_BITS; ++b) {
+        const bool bit = (d >> b) & 1;
+        const uint64_t bb = __ballot(valid && bit);
+        same &= bit ? bb : ~bb;
+      }
+      const int rank = __popcll(same & below);
+      if (valid && rank == 0) cnt8[wave][d][r] = (uint8_t)__popcll(same);
+      dr[r] = (uint32_t)d | ((uint32_t)rank << 8) | (valid ? 1u << 16 : 0u);
+    }
+    __builtin_amdgcn_wave_barrier();
+    // lane = digit: running offsets over the rounds
+    const uint4 cv = *reinterpret_cast<const uint4*>(&cnt8[wave][lane][0]);
+    const uint32_t cw[4] = {cv.x, cv.y, cv.z, cv.w};
+    int pre[ITEMS];
+    int tot = 0;
+#pragma unroll
+    for (int r = 0; r < ITEMS; ++r) {
+      pre[r] = tot;
+      tot += (int)((cw[r >> 2] >> ((r & 3) * 8)) & 0xffu);
+    }
+    table[lane * SORT_WAVES + wave] = tot;
     __syncthreads();
     {  // exclusive scan of the 1024 table entries, one per thread
       const int v = table[tid];
@@ -243,25 +279,12 @@ __global__ __launch_bounds__(1024) void sort_unique_fused_kernel(const int32_t* 
       table[tid] = wsum[wave] + inc - v;
     }
     __syncthreads();
-    for (int i0 = w0; i0 < w1; i0 += 64) {
-      const int i = i0 + lane;
-      const bool valid = i < w1;
-      uint32_t key = 0;
-      int d = 0;
-      if (valid) { key = buf[cur][i]; d = (key >> shift) & (RADIX - 1); }
-      uint64_t same = __ballot(valid);
+    const int base = table[lane * SORT_WAVES + wave];  // first output slot of (digit = lane, this wavefront)
 #pragma unroll
-      for (int b = 0; b < RADIX_BITS; ++b) {
-        const bool bit = (d >> b) & 1;
-        const uint64_t bb = __ballot(valid && bit);
-        same &= bit ? bb : ~bb;
-      }
-      int pos = 0;
-      if (valid) pos = table[d * SORT_WAVES + wave] + __popcll(same & below);
-      __builtin_amdgcn_wave_barrier();
-      if (valid && (same & below) == 0) table[d * SORT_WAVES + wave] += __popcll(same);
-      __builtin_amdgcn_wave_barrier();
-      if (valid) buf[cur ^ 1][pos] = key;
+    for (int r = 0; r < ITEMS; ++r) {
+      const int d = dr[r] & 0xff;
+      const int start = __shfl(base + pre[r], d);
+      if (dr[r] >> 16) buf[cur ^ 1][start + (int)((dr[r] >> 8) & 0xff)] = key[r];
     }
     __syncthreads();
     cur ^= 1;
