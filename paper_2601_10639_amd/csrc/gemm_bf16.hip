@@ -316,7 +316,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  // The fused epilogues read one gathered table row (and one saved activation row) per output
+  // row.  A few K tiles before the end of the main loop each lane touches the 128-byte lines its
+  // wavefront will need, so that they travel from HBM to L2 under the MFMA work instead of in a
+  // burst when all workgroups reach their epilogues together.
+  constexpr bool FUSED_EPI = (EPI == EPI_GATE || EPI == EPI_DH);
+  auto touch_epilogue_inputs = [&]() {
+    if (!FUSED_EPI) return;
+    const int ncol = n0 + wn * 128;
+    const int col = ncol < p.N ? ncol : 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int m = m0 + wm * 128 + h * 64 + lane;
+      const int mc = m < p.M ? m : p.M - 1;
+      int id = p.ids[mc];
+      if ((unsigned)id >= (unsigned)p.E_rows) id = id < 0 ? 0 : p.E_rows - 1;  // reported by the epilogue
+      const bf16_t* e = p.E + (size_t)id * p.N + col;
+      uint32_t j0, j1;
+      asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
+                   : "=&v"(j0), "=&v"(j1) : "v"(e) : "memory");
+      if (EPI == EPI_DH) {
+        const bf16_t* g = p.inG + (size_t)mc * p.N + col;
+        asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
+                     : "=&v"(j0), "=&v"(j1) : "v"(g) : "memory");
+      }
+    }
+  };
+  const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
   for (int kt = 0; kt + 1 < nk; kt += 2) {
+    if (FUSED_EPI && kt == touch_at) touch_epilogue_inputs();
     iteration(0);
     iteration(1);
   }
