@@ -7,6 +7,10 @@ in HBM: stem_ffn_forward (gate GEMM with fused SiLU*gather, down GEMM), stem_ffn
 stem_embed_sparse_adamw on the touched rows.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C1]
+
+Two more workloads measure the forward-only configurations (not the headline metric):
+--workload C4 times a decode step of 256 single tokens through 16 stacked layers, --workload C5
+[--ids zipf|uniform] the 65536-token forward with the table in pinned host memory.
 """
 from __future__ import annotations
 
@@ -30,7 +34,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--ids", default="zipf", choices=["zipf", "uniform"], help="id distribution for C5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -52,6 +57,10 @@ def main() -> int:
     L.lib()  # fails loudly if libstem.so has not been built
     dev = "cuda:0"
     shape = inputs.SHAPES[args.workload]
+    if args.workload == "C4":
+        return bench_decode(args, shape, dev)
+    if args.workload == "C5":
+        return bench_host_table(args, shape, dev)
     T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
     bf16 = shape.dtype == "bf16"
     dt = inputs.torch_dtype(shape.dtype)
@@ -177,6 +186,165 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, inp, args.cpu_sample_tokens, hp)
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
+def _median_ms(fn, steps, warmup):
+    """Wall-clock per call (device idle before and after each), median / p10 / p90 in ms."""
+    import numpy as np
+    import torch
+    for _ in range(warmup):
+        fn()
+    ts = []
+    for _ in range(steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        ts.append((time.perf_counter() - t0) * 1e3)
+    ts = np.sort(np.asarray(ts))
+    return float(np.median(ts)), float(ts[int(0.1 * (len(ts) - 1))]), float(ts[int(round(0.9 * (len(ts) - 1)))])
+
+
+def bench_decode(args, shape, dev):
+    """One decode step: T single tokens through n_layers stacked layers (each with its own weights
+    and table), residual stream in bf16.  The residual add between layers is a torch op; the
+    layers are stem_ffn_forward calls.  HBM-bound on the weights: 2*d*F*2 bytes per layer."""
+    import torch
+
+    from paper_2601_10639_amd import inputs, stemlib as L
+
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    n_layers = 16
+    ids_np = inputs.zipf_ids(T, V, seed=31)
+    ids = torch.from_numpy(ids_np).to(dev)
+    U = len(set(ids_np.tolist()))
+    ctx = L.stem_create(d, F, V, L.STEM_BF16, T, 0)
+    Wg = [inputs.normal((F, d), 0.02, 100 + 3 * l, torch.bfloat16, dev) for l in range(n_layers)]
+    Wd = [inputs.normal((d, F), 0.02, 101 + 3 * l, torch.bfloat16, dev) for l in range(n_layers)]
+    E = [inputs.normal((V, F), 0.02, 102 + 3 * l, torch.bfloat16, dev) for l in range(n_layers)]
+    x0 = inputs.normal((T, d), 1.0, 32, torch.bfloat16, dev)
+    x = x0.clone()
+    y = torch.empty_like(x0)
+
+    def step():
+        x.copy_(x0)
+        for l in range(n_layers):
+            L.stem_ffn_forward(ctx, x, ids, Wg[l], Wd[l], E[l], y)
+            x.add_(y)
+
+    steps = max(args.steps, 50)
+    med, p10, p90 = _median_ms(step, steps, max(args.warmup, 10))
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    L.stem_sync_status(ctx)
+    L.stem_profile_enable(ctx, True)
+    L.stem_profile_reset(ctx)
+    for _ in range(10):
+        step()
+    prof = L.stem_profile_read(ctx)
+    L.stem_profile_enable(ctx, False)
+    kernels = {k: {"avg_ms": round(v[0] / v[1], 5), "launches": v[1]} for k, v in prof.items()}
+    kern_ms = sum(v[0] for v in prof.values()) / 10
+    weight_bytes = n_layers * 2 * d * F * 2
+    row_bytes = n_layers * U * F * 2
+    act_bytes = n_layers * (2 * T * d * 2 + 2 * T * F * 2)
+    algo = weight_bytes + row_bytes + act_bytes
+    out = {
+        "metric": "STEM FFN decode step latency, 16 stacked layers", "value": round(ms * 1e3, 1), "unit": "us",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "layers": n_layers,
+                   "n_uniq": U, "ids": "Zipf(s=1.1)", "step": "16 x (forward + residual add)"},
+        "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4),
+                       "back_to_back": round(ms, 4), "kernels_only": round(kern_ms, 4)},
+        "roofline": {"bound": "hbm", "kernel": "decode step (all kernels)",
+                     "achieved": round(algo / (kern_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(algo / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
+                     "bytes": {"weights": weight_bytes, "table_rows": row_bytes, "activations": act_bytes}},
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
+def bench_host_table(args, shape, dev):
+    """Forward of one layer over a long sequence with the table in pinned host memory: de-duplicate
+    the ids, copy the distinct rows over the host link on a side stream while the gate GEMM runs,
+    then the gather epilogue and the down GEMM.  Also times the same forward with a device-resident
+    table (what the copy exposes) and a plain pinned host-to-device copy (the link's rate)."""
+    import torch
+
+    from paper_2601_10639_amd import inputs, stemlib as L
+
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    ids_np = inputs.zipf_ids(T, V, seed=51) if args.ids == "zipf" else inputs.uniform_ids(T, V, seed=52)
+    ids_host = torch.from_numpy(ids_np)
+    U = len(set(ids_np.tolist()))
+    ctx = L.stem_create(d, F, V, L.STEM_BF16, T, 0)
+    E_host = inputs.normal((V, F), 0.02, 53, torch.bfloat16, "cpu").pin_memory()
+    x = inputs.normal((T, d), 1.0, 54, torch.bfloat16, dev)
+    Wg = inputs.normal((F, d), 0.02, 55, torch.bfloat16, dev)
+    Wd = inputs.normal((d, F), 0.02, 56, torch.bfloat16, dev)
+    y = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
+    E_compact = torch.empty(U + 8, F, dtype=torch.bfloat16, device=dev)
+    remap = torch.empty(T, dtype=torch.int32, device=dev)
+    ids_dev = ids_host.to(dev)
+    E_dev = E_host.to(dev)
+    dedup_ms = []
+
+    def step():
+        t0 = time.perf_counter()
+        n, ev = L.stem_prefetch_rows(ctx, E_host, ids_host, E_compact, remap)
+        dedup_ms.append((time.perf_counter() - t0) * 1e3)
+        L.stem_ffn_forward(ctx, x, remap, Wg, Wd, E_compact, y, wait_event=ev, E_rows=n)
+
+    def step_resident():
+        L.stem_ffn_forward(ctx, x, ids_dev, Wg, Wd, E_dev, y)
+
+    steps, warm = args.steps, args.warmup
+    med, p10, p90 = _median_ms(step, steps, warm)
+    del dedup_ms[:warm]
+    res_med, _, _ = _median_ms(step_resident, steps, warm)
+    L.stem_sync_status(ctx)
+    # the link itself: one contiguous pinned copy of as many bytes as the rows
+    nbytes = U * F * 2
+    flat = E_host.view(-1)[: U * F]
+    dst = torch.empty(U * F, dtype=torch.bfloat16, device=dev)
+    link_med, _, _ = _median_ms(lambda: dst.copy_(flat, non_blocking=True), 5, 2)
+    L.stem_profile_enable(ctx, True)
+    L.stem_profile_reset(ctx)
+    for _ in range(3):
+        step()
+    prof = L.stem_profile_read(ctx)
+    L.stem_profile_enable(ctx, False)
+    kernels = {k: {"avg_ms": round(v[0] / v[1], 5), "launches": v[1]} for k, v in prof.items()}
+    copy_ms = kernels.get("row_copy", {}).get("avg_ms")
+    out = {
+        "metric": "STEM FFN forward tokens/s, host-resident table", "value": round(T / (med * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(med, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "n_uniq": U,
+                   "ids": "Zipf(s=1.1)" if args.ids == "zipf" else "uniform",
+                   "step": "dedup + row copy over the host link (side stream) + forward"},
+        "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4),
+                       "device_resident_forward": round(res_med, 4), "exposed_by_host_table": round(med - res_med, 4),
+                       "host_dedup_and_enqueue": round(sorted(dedup_ms)[len(dedup_ms) // 2], 4)},
+        "roofline": {"bound": "host link", "kernel": "row_copy", "achieved": None if not copy_ms else
+                     round(nbytes / (copy_ms * 1e-3) / 1e9, 2), "peak": round(nbytes / (link_med * 1e-3) / 1e9, 2),
+                     "unit": "GB/s", "frac": None if not copy_ms else round(link_med / copy_ms, 4), "traffic": None,
+                     "bytes": nbytes, "peak_is": "measured contiguous pinned host-to-device copy of the same size"},
+        "kernels": kernels,
+    }
     print(json.dumps(out))
     ctx.close()
     return 0

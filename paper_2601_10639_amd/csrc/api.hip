@@ -20,7 +20,7 @@ const char* const kKernelNames[K_COUNT_] = {
     "gemm_gate_fused", "gemm_gate_plain", "gemm_down",    "gemm_dh_fused", "gemm_dx",      "gemm_dw_down",
     "gemm_dw_gate",    "silu_gather",     "dh_epilogue",  "sort_count",    "sort_scan",    "sort_scatter",
     "sort_fused",      "unique",          "seg_reduce",   "seg_combine",   "sparse_adamw", "row_copy",
-    "transpose"};
+    "transpose",       "splitk_reduce"};
 
 stem_status fail(stem_ctx* c, stem_status st, const char* fmt, ...) {
   char* buf = c ? c->err : g_create_err;
@@ -70,7 +70,7 @@ void release(stem_ctx* c) {
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
   (void)hipFree(c->H_ws); (void)hipFree(c->dG_ws); (void)hipFree(c->dH_ws);
-  (void)hipFree(c->WT_ws); (void)hipFree(c->actT_ws);
+  (void)hipFree(c->WT_ws); (void)hipFree(c->actT_ws); (void)hipFree(c->splitk_ws);
   for (int i = 0; i < 2; ++i) { (void)hipFree(c->sort_keys[i]); (void)hipFree(c->sort_vals[i]); }
   (void)hipFree(c->sort_counts); (void)hipFree(c->seg_of); (void)hipFree(c->seg_part);
   (void)hipFree(c->uniq_dev);
@@ -139,6 +139,7 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
   if (desc->dtype == STEM_BF16) {
     ok(hipMalloc(&c->WT_ws, (size_t)desc->d_ff * desc->d_model * 2));
     ok(hipMalloc(&c->actT_ws, std::max<size_t>((size_t)desc->d_model * ((max_tokens + 63) / 64 * 64) * 2, 16)));
+    ok(hipMalloc(reinterpret_cast<void**>(&c->splitk_ws), STEM_SPLITK_WS_BYTES));
   }
   for (int i = 0; i < 2; ++i) {
     ok(dmalloc(&c->sort_keys[i], (size_t)max_tokens));
@@ -203,13 +204,18 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
     a.B = static_cast<const bf16_t*>(W_gate); a.ldb = d;
     a.M = (int)T; a.N = F; a.K = d;
     a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows; a.flag = c->flag;
+    // A decode-sized call (a few hundred tokens) takes the few-row kernel: 128x64 tiles, the down
+    // product split along K so that both launches fill the chip.
+    const bool few = T <= STEM_SKINNY_MAX_M;
     if (!wait_event) {
       a.outG = static_cast<bf16_t*>(save_G); a.outH = static_cast<bf16_t*>(H);
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE, OP_KC, OP_KC, EPI_GATE, a, s));
+      if (few) HIP_TRY(c, stem_gemm_skinny_bf16(c, K_GEMM_GATE, EPI_GATE, a, s));
+      else HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE, OP_KC, OP_KC, EPI_GATE, a, s));
     } else {
       void* G = save_G ? save_G : c->dG_ws;
       a.C = G;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE_PLAIN, OP_KC, OP_KC, EPI_BF16, a, s));
+      if (few) HIP_TRY(c, stem_gemm_skinny_bf16(c, K_GEMM_GATE_PLAIN, EPI_BF16, a, s));
+      else HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE_PLAIN, OP_KC, OP_KC, EPI_BF16, a, s));
       HIP_TRY(c, hipStreamWaitEvent(s, static_cast<hipEvent_t>(wait_event), 0));
       HIP_TRY(c, stem_silu_gather(c, 1, G, ids, E, (int)E_rows, H, T, F, s));
     }
@@ -217,7 +223,14 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
     b.A = static_cast<const bf16_t*>(H); b.lda = F;
     b.B = static_cast<const bf16_t*>(W_down); b.ldb = F;
     b.M = (int)T; b.N = d; b.K = F; b.C = y; b.flag = c->flag;
-    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, EPI_BF16, b, s));
+    if (few) {
+      b.ksplit = stem_gemm_skinny_ksplit(b.M, b.N, b.K);
+      b.ws = c->splitk_ws;
+      if ((size_t)b.ksplit * b.M * b.N * 4 > STEM_SPLITK_WS_BYTES) b.ksplit = 1;
+      HIP_TRY(c, stem_gemm_skinny_bf16(c, K_GEMM_DOWN, b.ksplit > 1 ? EPI_SPLITK : EPI_BF16, b, s));
+    } else {
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, EPI_BF16, b, s));
+    }
   } else {
     float* G = static_cast<float*>(save_G ? save_G : c->dG_ws);
     HIP_TRY(c, stem_sgemm(c, wait_event ? K_GEMM_GATE_PLAIN : K_GEMM_GATE, static_cast<const float*>(x), d, 1,

@@ -320,7 +320,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   // row.  A few K tiles before the end of the main loop each lane touches the 128-byte lines its
   // wavefront will need, so that they travel from HBM to L2 under the MFMA work instead of in a
   // burst when all workgroups reach their epilogues together.
+  // The touching loads return asynchronously into their destination registers, so these stay
+  // reserved (never reused by the compiler) until the wait that follows the main loop.
   constexpr bool FUSED_EPI = (EPI == EPI_GATE || EPI == EPI_DH);
+  uint32_t touched[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   auto touch_epilogue_inputs = [&]() {
     if (!FUSED_EPI) return;
     const int ncol = n0 + wn * 128;
@@ -332,13 +335,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       int id = p.ids[mc];
       if ((unsigned)id >= (unsigned)p.E_rows) id = id < 0 ? 0 : p.E_rows - 1;  // reported by the epilogue
       const bf16_t* e = p.E + (size_t)id * p.N + col;
-      uint32_t j0, j1;
       asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
-                   : "=&v"(j0), "=&v"(j1) : "v"(e) : "memory");
+                   : "=&v"(touched[4 * h]), "=&v"(touched[4 * h + 1]) : "v"(e) : "memory");
       if (EPI == EPI_DH) {
         const bf16_t* g = p.inG + (size_t)mc * p.N + col;
         asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
-                     : "=&v"(j0), "=&v"(j1) : "v"(g) : "memory");
+                     : "=&v"(touched[4 * h + 2]), "=&v"(touched[4 * h + 3]) : "v"(g) : "memory");
       }
     }
   };
@@ -350,6 +352,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   }
   if (nk & 1) iteration(0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (FUSED_EPI)   // end of the touched registers' reservation
+    asm volatile("" ::"v"(touched[0]), "v"(touched[1]), "v"(touched[2]), "v"(touched[3]), "v"(touched[4]),
+                 "v"(touched[5]), "v"(touched[6]), "v"(touched[7]));
   __syncthreads();
 
   // ---- epilogue: per wavefront, 32 rows at a time through LDS ----------------------------

@@ -28,6 +28,7 @@ enum StemKernelId {
   K_ADAMW,
   K_ROW_COPY,        // host-resident rows -> compact device table
   K_TRANSPOSE,       // bf16 operand transposes ahead of the backward GEMMs
+  K_SPLITK_REDUCE,   // sum of the split-K partial products of a few-row GEMM
   K_COUNT_
 };
 
@@ -45,6 +46,7 @@ struct stem_ctx {
   void* dH_ws;           // [max_tokens, F] fp32, STEM_F32 only
   void* WT_ws;           // [F*d] bf16: a weight matrix transposed (backward)
   void* actT_ws;         // [d, round_up(max_tokens, 64)] bf16: dy or x transposed (backward)
+  float* splitk_ws;      // STEM_SPLITK_WS_BYTES: fp32 partial products of the few-row GEMMs
   int32_t* sort_keys[2]; // [max_tokens]
   int32_t* sort_vals[2]; // [max_tokens]
   int32_t* sort_counts;  // [64 * waves]
@@ -97,7 +99,8 @@ enum GemmEpilogue {
   EPI_BF16 = 0, // C -> bf16 [M,N]
   EPI_F32,      // C -> fp32 [M,N], optional +=
   EPI_GATE,     // G (optional) and H = SiLU(C) * E[ids[m], n], both bf16
-  EPI_DH        // dU = C * SiLU(G), dG = C * E[ids[m], n] * SiLU'(G), both bf16
+  EPI_DH,       // dU = C * SiLU(G), dG = C * E[ids[m], n] * SiLU'(G), both bf16
+  EPI_SPLITK    // few-row kernel only: fp32 partial products per k slice, summed into bf16 C
 };
 
 struct GemmArgs {
@@ -117,9 +120,22 @@ struct GemmArgs {
   bf16_t* outdU;   // EPI_DH
   bf16_t* outdG;   // EPI_DH
   int32_t* flag;
+  float* ws;       // EPI_SPLITK: [ksplit][M][N] fp32
+  int ksplit;      // EPI_SPLITK: number of k slices
+  int mt, nt;      // few-row kernel: tile counts and exact float reciprocals, filled in by the launcher
+  float inv_mt, inv_per_z;
 };
 
 hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const GemmArgs& a, hipStream_t s);
+
+// ---- few-row bf16 GEMM (gemm_skinny_bf16.hip): both operands K-contiguous, K % 64 == 0 --------
+// 128x64 tiles; used when M is small enough that 256x256 tiles would leave most of the chip idle.
+#define STEM_SKINNY_MAX_M 512
+#define STEM_SPLITK_WS_BYTES ((size_t)8 << 20)   // >= ksplit * M * N * 4 whenever ksplit > 1
+// k slices that bring the launch to about one workgroup per compute unit (1 = no split)
+int stem_gemm_skinny_ksplit(int M, int N, int K);
+// epi: EPI_BF16, EPI_GATE, or EPI_SPLITK (a.ksplit slices through a.ws, then summed into a.C)
+hipError_t stem_gemm_skinny_bf16(stem_ctx* ctx, int kid, int epi, const GemmArgs& a, hipStream_t s);
 
 // ---- fp32 path and element-wise kernels (kernels_f32.hip) -------------------------
 // C[m,n] (+)= sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]

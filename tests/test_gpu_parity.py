@@ -108,6 +108,32 @@ def test_bf16_all_tokens_same_id_and_all_distinct():
     _pipeline_case(s, 520, seed=6, ids=np.random.default_rng(0).permutation(700)[:520].astype(np.int32))
 
 
+@pytest.mark.parametrize("T,d,F", [(1, 64, 64), (37, 192, 320), (128, 256, 576), (129, 128, 1024), (256, 192, 4096),
+                                   (300, 64, 2112), (512, 128, 640), (513, 128, 640)])
+def test_bf16_few_row_forward(T, d, F):
+    """Decode-sized calls take the 128x64-tile kernel (the down product split along K when d_ff is
+    long: 2 slices at F=1024, 8 at 4096, 4 uneven ones at 2112); T=513 is the first size on the
+    256x256-tile kernel again.  Forward only, with and without the saved G and H."""
+    s = inputs.StemShape("bf16-few-rows", d, F, 500, 1, T, "bf16")
+    inp = inputs.layer_inputs(s, seed=7, device=DEV, tokens=T)
+    ctx = Hn.make_ctx(s, T)
+    dt = inp["x"].dtype
+    y = torch.empty(T, d, dtype=dt, device=DEV)
+    y2 = torch.empty(T, d, dtype=dt, device=DEV)
+    G = torch.empty(T, F, dtype=dt, device=DEV)
+    H = torch.empty(T, F, dtype=dt, device=DEV)
+    L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], y, G, H)
+    L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], y2)
+    L.stem_sync_status(ctx)
+    f64 = {k: inputs.to_f64(v) for k, v in inp.items() if k != "ids"}
+    ref, fw = O.ffn_forward(f64["x"], inp["ids"].cpu().numpy(), f64["W_gate"], f64["W_down"], f64["E"])
+    errs = {"y": Hn.max_rel(y.float().cpu(), ref), "G": Hn.max_rel(G.float().cpu(), fw["g"]),
+            "H": Hn.max_rel(H.float().cpu(), fw["h"])}
+    assert all(v <= Hn.TOL["bf16"] for v in errs.values()), errs
+    assert torch.equal(y, y2)
+    ctx.close()
+
+
 @pytest.mark.parametrize("T,V", [(1, 1), (2, 2), (64, 5), (4096, 50304), (4097, 128256), (16384, 128256),
                                  (65536, 128256), (70001, 64), (5000, (1 << 20) + 3)])
 def test_sort_unique_offsets_bit_exact(T, V):
