@@ -92,8 +92,12 @@ stem_status stem_sync_status(stem_ctx* ctx, void* stream);
  * wait_event: NULL, or a hipEvent_t (as returned by stem_prefetch_rows) that marks E's
  * rows as ready.  When given, the gate GEMM is enqueued first, `stream` then waits on
  * the event, and the SiLU*gather runs as a separate kernel before the down GEMM, so
- * the row copy overlaps the gate GEMM.  When NULL the gather is fused into the gate
- * GEMM's epilogue. */
+ * the row copy overlaps the gate GEMM.  When the event is the one the context's last
+ * stem_prefetch_rows returned for the same T (bf16 contexts), the wait is finer: the
+ * rows were copied in order of first use with an event per chunk of tokens, and the
+ * gather and the down GEMM of each chunk start as soon as that chunk's rows are there.
+ * When NULL the gather is fused into the gate GEMM's epilogue.  Calls of at most 512
+ * tokens (a decode step) use 128x64 tiles so that both products fill the chip. */
 stem_status stem_ffn_forward(stem_ctx* ctx, const void* x, const int32_t* ids, const void* W_gate,
                              const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y,
                              void* save_G, void* save_H, void* wait_event, void* stream);
@@ -144,7 +148,8 @@ stem_status stem_embed_sparse_adamw(stem_ctx* ctx, const int32_t* uniq_ids, cons
 
 /* E_host [V,F] lives in pinned host memory (hipHostMalloc); ids_host [T] is host memory.
  * De-duplicates ids on the host (distinct ids ascending), copies row uniq[j] of E_host to
- * E_compact[j] (device, capacity `cap` rows) on the context's side stream, and writes
+ * E_compact[j] (device, capacity `cap` rows) on the context's side stream (rows travel in
+ * the order in which the tokens first use them), and writes
  * remap[i] = j with uniq[j] == ids[i] (device [T]) there too, so that
  *   stem_ffn_forward(E = E_compact, ids = remap, E_rows = *n_uniq_host, wait_event = *ready_event)
  * is the same layer.  *n_uniq_host (host) is valid on return; uniq_ids_host (host, may be

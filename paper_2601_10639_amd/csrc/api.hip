@@ -74,6 +74,10 @@ void release(stem_ctx* c) {
   for (int i = 0; i < 2; ++i) { (void)hipFree(c->sort_keys[i]); (void)hipFree(c->sort_vals[i]); }
   (void)hipFree(c->sort_counts); (void)hipFree(c->seg_of); (void)hipFree(c->seg_part);
   (void)hipFree(c->uniq_dev);
+  (void)hipFree(c->order_dev);
+  if (c->order_pinned) (void)hipHostFree(c->order_pinned);
+  for (int i = 0; i < STEM_PF_MAX_CHUNKS; ++i)
+    if (c->pf_ev[i]) (void)hipEventDestroy(c->pf_ev[i]);
   if (c->flag) (void)hipHostFree(c->flag);
   if (c->uniq_pinned) (void)hipHostFree(c->uniq_pinned);
   if (c->remap_pinned) (void)hipHostFree(c->remap_pinned);
@@ -149,6 +153,9 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
   ok(dmalloc(&c->seg_of, (size_t)max_tokens));
   ok(dmalloc(&c->seg_part, (size_t)stem_seg_chunks(std::max<int64_t>(max_tokens, 1)) * 2 * desc->d_ff));
   ok(dmalloc(&c->uniq_dev, (size_t)max_tokens));
+  ok(dmalloc(&c->order_dev, 2 * (size_t)max_tokens));
+  ok(hipHostMalloc(reinterpret_cast<void**>(&c->order_pinned), std::max<size_t>(max_tokens, 1) * 8, hipHostMallocDefault));
+  for (int i = 0; i < STEM_PF_MAX_CHUNKS; ++i) ok(hipEventCreateWithFlags(&c->pf_ev[i], hipEventDisableTiming));
   ok(hipHostMalloc(reinterpret_cast<void**>(&c->flag), 64, hipHostMallocDefault));
   ok(hipHostMalloc(reinterpret_cast<void**>(&c->uniq_pinned), std::max<size_t>(max_tokens, 1) * 4, hipHostMallocDefault));
   ok(hipHostMalloc(reinterpret_cast<void**>(&c->remap_pinned), std::max<size_t>(max_tokens, 1) * 4, hipHostMallocDefault));
@@ -207,6 +214,10 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
     // A decode-sized call (a few hundred tokens) takes the few-row kernel: 128x64 tiles, the down
     // product split along K so that both launches fill the chip.
     const bool few = T <= STEM_SKINNY_MAX_M;
+    GemmArgs b = {};
+    b.A = static_cast<const bf16_t*>(H); b.lda = F;
+    b.B = static_cast<const bf16_t*>(W_down); b.ldb = F;
+    b.M = (int)T; b.N = d; b.K = F; b.C = y; b.flag = c->flag;
     if (!wait_event) {
       a.outG = static_cast<bf16_t*>(save_G); a.outH = static_cast<bf16_t*>(H);
       if (few) HIP_TRY(c, stem_gemm_skinny_bf16(c, K_GEMM_GATE, EPI_GATE, a, s));
@@ -216,13 +227,25 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
       a.C = G;
       if (few) HIP_TRY(c, stem_gemm_skinny_bf16(c, K_GEMM_GATE_PLAIN, EPI_BF16, a, s));
       else HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE_PLAIN, OP_KC, OP_KC, EPI_BF16, a, s));
+      if (wait_event == c->ready && c->pf_chunks > 1 && c->pf_T == T) {
+        // Rows arrive in order of first use: run the gather and the down product chunk by chunk,
+        // each as soon as the rows its tokens need are there, the later rows still on the link.
+        for (int k = 0; k < c->pf_chunks; ++k) {
+          const int64_t t0 = k * c->pf_chunk_tokens, tn = std::min(c->pf_chunk_tokens, T - t0);
+          HIP_TRY(c, hipStreamWaitEvent(s, c->pf_ev[k], 0));
+          HIP_TRY(c, stem_silu_gather(c, 1, static_cast<const bf16_t*>(G) + t0 * F, ids + t0, E, (int)E_rows,
+                                      static_cast<bf16_t*>(H) + t0 * F, tn, F, s));
+          GemmArgs bk = b;
+          bk.A = static_cast<const bf16_t*>(H) + t0 * F;
+          bk.C = static_cast<bf16_t*>(y) + t0 * d;
+          bk.M = (int)tn;
+          HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, EPI_BF16, bk, s));
+        }
+        return STEM_OK;
+      }
       HIP_TRY(c, hipStreamWaitEvent(s, static_cast<hipEvent_t>(wait_event), 0));
       HIP_TRY(c, stem_silu_gather(c, 1, G, ids, E, (int)E_rows, H, T, F, s));
     }
-    GemmArgs b = {};
-    b.A = static_cast<const bf16_t*>(H); b.lda = F;
-    b.B = static_cast<const bf16_t*>(W_down); b.ldb = F;
-    b.M = (int)T; b.N = d; b.K = F; b.C = y; b.flag = c->flag;
     if (few) {
       b.ksplit = stem_gemm_skinny_ksplit(b.M, b.N, b.K);
       b.ws = c->splitk_ws;
@@ -413,10 +436,41 @@ stem_status stem_prefetch_rows(stem_ctx* c, const void* E_host, const int32_t* i
       for (int64_t j = 0; j < U; ++j) c->slot[c->uniq_pinned[j]] = (int32_t)j;
     }
   }
-  for (int64_t i = 0; i < T; ++i) c->remap_pinned[i] = c->slot[ids_host[i]];
+  // One pass over the tokens: the compact slot of every token, and the distinct rows in order of
+  // first use, so that the rows the first tokens need cross the link first.  Long batches are cut
+  // into chunks; an event after each chunk's rows lets the forward
+  // call run the gather and the down product of a chunk while later rows are still on the link.
+  // Chunk size: the down product of one chunk is about one round of 256x256 tiles
+  // (STEM_PF_CHUNK_TILES); whole multiples of that if the batch is very long.
+  const int64_t tile_cols = (c->desc.d_model + 255) / 256;
+  int64_t chunk_tokens = std::max<int64_t>(1, STEM_PF_CHUNK_TILES / tile_cols) * 256;
+  chunk_tokens *= std::max<int64_t>(1, ((T + chunk_tokens - 1) / chunk_tokens + STEM_PF_MAX_CHUNKS - 1) / STEM_PF_MAX_CHUNKS);
+  int nchunks = (int)((T + chunk_tokens - 1) / chunk_tokens);
+  if (nchunks < 2) { nchunks = 1; chunk_tokens = std::max<int64_t>(T, 1); }
+  int64_t chunk_end[STEM_PF_MAX_CHUNKS] = {0};
+  int32_t* src_row = c->order_pinned;
+  int32_t* dst_slot = c->order_pinned + c->max_tokens;
+  {
+    int64_t k = 0;
+    for (int64_t i = 0; i < T; ++i) {
+      const int32_t t = ids_host[i];
+      int32_t v = c->slot[t];
+      if (v >= 0) {            // first use of this row
+        src_row[k] = t;
+        dst_slot[k] = v;
+        ++k;
+        c->slot[t] = -2 - v;   // seen; the slot stays recoverable
+      } else {
+        v = -2 - v;
+      }
+      c->remap_pinned[i] = v;
+      if ((i + 1) % chunk_tokens == 0 || i + 1 == T) chunk_end[std::min<int64_t>(i / chunk_tokens, nchunks - 1)] = k;
+    }
+  }
   for (int64_t j = 0; j < U; ++j) c->slot[c->uniq_pinned[j]] = -1;
   *n_uniq_host = U;
   if (uniq_ids_host) memcpy(uniq_ids_host, c->uniq_pinned, (size_t)std::min<int64_t>(U, cap) * 4);
+  c->pf_chunks = 0;
   if (U > cap)
     return fail(c, STEM_ERR_WORKSPACE, "stem_prefetch_rows: %lld distinct ids but E_compact holds %lld rows",
                 (long long)U, (long long)cap);
@@ -452,8 +506,16 @@ stem_status stem_prefetch_rows(stem_ctx* c, const void* E_host, const int32_t* i
       HIP_TRY(c, hipEventRecord(c->pack_done[chunk & 1], c->side));
     }
   } else if (U > 0) {
-    HIP_TRY(c, hipMemcpyAsync(c->uniq_dev, c->uniq_pinned, (size_t)U * 4, hipMemcpyHostToDevice, c->side));
-    HIP_TRY(c, stem_copy_rows_kernel(c, E_host, c->uniq_dev, U, (int64_t)row_bytes, E_compact, c->side));
+    HIP_TRY(c, hipMemcpyAsync(c->order_dev, src_row, (size_t)U * 4, hipMemcpyHostToDevice, c->side));
+    HIP_TRY(c, hipMemcpyAsync(c->order_dev + c->max_tokens, dst_slot, (size_t)U * 4, hipMemcpyHostToDevice, c->side));
+    int64_t k0 = 0;
+    for (int k = 0; k < nchunks; ++k) {
+      HIP_TRY(c, stem_copy_rows_kernel(c, E_host, c->order_dev + k0, c->order_dev + c->max_tokens + k0,
+                                       chunk_end[k] - k0, (int64_t)row_bytes, E_compact, c->side));
+      k0 = chunk_end[k];
+      if (nchunks > 1) HIP_TRY(c, hipEventRecord(c->pf_ev[k], c->side));
+    }
+    if (nchunks > 1) { c->pf_chunks = nchunks; c->pf_T = T; c->pf_chunk_tokens = chunk_tokens; }
   }
   HIP_TRY(c, hipEventRecord(c->ready, c->side));
   *ready_event = c->ready;

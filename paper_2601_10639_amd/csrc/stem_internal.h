@@ -33,6 +33,8 @@ enum StemKernelId {
 };
 
 #define STEM_MAX_PROF_EVENTS 8192
+#define STEM_PF_MAX_CHUNKS 16
+#define STEM_PF_CHUNK_TILES 256     // one round of 256x256 down-product tiles per chunk (measured better than 224 and 512)
 
 struct stem_ctx {
   stem_layer_desc desc;
@@ -61,6 +63,12 @@ struct stem_ctx {
   int32_t* uniq_pinned;  // pinned host [max_tokens]
   int32_t* remap_pinned; // pinned host [max_tokens]
   int32_t* uniq_dev;     // device [max_tokens]
+  int32_t* order_pinned; // pinned host [2 * max_tokens]: table row, then compact slot, in order of first use
+  int32_t* order_dev;    // device [2 * max_tokens]
+  // chunks of the last prefetch: tokens [k * pf_chunk_tokens, ...) need only rows copied before pf_ev[k]
+  int pf_chunks;         // 0 = the last prefetch recorded no per-chunk events
+  int64_t pf_T, pf_chunk_tokens;
+  hipEvent_t pf_ev[STEM_PF_MAX_CHUNKS];
   char* pack_pinned;     // pinned host staging for the memcpy mode
   size_t pack_bytes;
   hipEvent_t pack_done[2];
@@ -166,5 +174,6 @@ hipError_t stem_adamw(stem_ctx* ctx, int is_bf16, const int32_t* uniq_ids, const
                       const stem_adamw_hparams& hp, hipStream_t s);
 
 // ---- host-resident rows (prefetch.hip) ----------------------------------------------
-hipError_t stem_copy_rows_kernel(stem_ctx* ctx, const void* E_host, const int32_t* uniq_dev, int64_t n,
-                                 int64_t row_bytes, void* E_compact, hipStream_t s);
+// E_compact[dst_slot[k]] = E_host[src_row[k]] for k in [0, n)
+hipError_t stem_copy_rows_kernel(stem_ctx* ctx, const void* E_host, const int32_t* src_row, const int32_t* dst_slot,
+                                 int64_t n, int64_t row_bytes, void* E_compact, hipStream_t s);

@@ -182,6 +182,17 @@ def test_prefetch_rows_small(dtype, mode):
     assert Hn.max_rel(y.float().cpu(), ref) <= Hn.TOL[dtype]
 
 
+def test_prefetch_rows_chunked_with_ragged_last_chunk():
+    """d_model 2048 gives chunks of 8192 tokens: 20000 tokens are two full chunks and one of 3616,
+    each waiting only for the rows its tokens use first.  Every token is checked."""
+    T = 20000
+    shape = inputs.StemShape("host-chunked", 2048, 128, 5000, 1, T, "bf16")
+    ids_np = inputs.uniform_ids(T, 5000, seed=43)
+    x, Wg, Wd, E_host, y, n = _prefetch_case(shape, T, ids_np, seed=44)
+    ref, _ = O.ffn_forward(inputs.to_f64(x), ids_np, inputs.to_f64(Wg), inputs.to_f64(Wd), inputs.to_f64(E_host))
+    assert Hn.max_rel(y.float().cpu(), ref) <= Hn.TOL["bf16"]
+
+
 def test_prefetch_rows_errors():
     shape = inputs.StemShape("host-err", 64, 64, 100, 1, 50, "bf16")
     ctx = Hn.make_ctx(shape, 50)
