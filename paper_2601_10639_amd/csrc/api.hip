@@ -70,7 +70,7 @@ void release(stem_ctx* c) {
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
   (void)hipFree(c->H_ws); (void)hipFree(c->dG_ws); (void)hipFree(c->dH_ws);
-  (void)hipFree(c->WT_ws); (void)hipFree(c->actT_ws); (void)hipFree(c->splitk_ws);
+  (void)hipFree(c->WT_ws); (void)hipFree(c->actT_ws); (void)hipFree(c->splitk_ws); (void)hipFree(c->dw_ws);
   for (int i = 0; i < 2; ++i) { (void)hipFree(c->sort_keys[i]); (void)hipFree(c->sort_vals[i]); }
   (void)hipFree(c->sort_counts); (void)hipFree(c->seg_of); (void)hipFree(c->seg_part);
   (void)hipFree(c->uniq_dev);
@@ -144,6 +144,13 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
     ok(hipMalloc(&c->WT_ws, (size_t)desc->d_ff * desc->d_model * 2));
     ok(hipMalloc(&c->actT_ws, std::max<size_t>((size_t)desc->d_model * ((max_tokens + 63) / 64 * 64) * 2, 16)));
     ok(hipMalloc(reinterpret_cast<void**>(&c->splitk_ws), STEM_SPLITK_WS_BYTES));
+    // Weight gradients are [d,F] outputs with K = T: a narrow layer has fewer 256x256 tiles than the
+    // chip has compute units, so its K range is cut into slices (at most 8, at most ~256 workgroups).
+    const int dw_tiles = ((desc->d_model + 255) / 256) * ((desc->d_ff + 255) / 256);
+    c->dw_ksplit = 1;
+    while (c->dw_ksplit < 8 && dw_tiles * c->dw_ksplit * 2 <= 256) c->dw_ksplit *= 2;
+    if (c->dw_ksplit > 1)
+      ok(hipMalloc(reinterpret_cast<void**>(&c->dw_ws), (size_t)c->dw_ksplit * desc->d_model * desc->d_ff * 4));
   }
   for (int i = 0; i < 2; ++i) {
     ok(dmalloc(&c->sort_keys[i], (size_t)max_tokens));
@@ -302,6 +309,8 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
     bf16_t* WT = static_cast<bf16_t*>(c->WT_ws);
     bf16_t* actT = static_cast<bf16_t*>(c->actT_ws);
     const int ldT = (int)((T + 63) / 64 * 64);
+    int dw_split = c->dw_ksplit;   // K slices of the weight-gradient GEMMs: at least 8 K tiles each
+    while (dw_split > 1 && ldT / 64 / dw_split < 8) dw_split /= 2;
     // The weight operands of the two activation-gradient products are needed K-contiguous:
     // transposing a [d,F] matrix costs a few percent of the product it feeds.
     {  // dH = dy W_down, fused into dU and dG;  W_down^T is [F,d]
@@ -318,6 +327,7 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
       GemmArgs a = {};
       a.A = actT; a.lda = ldT; a.B = Hb; a.ldb = F;
       a.M = d; a.N = F; a.K = ldT; a.K_mc = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
+      a.ksplit = dw_split; a.ws = c->dw_ws;
       HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_KC, OP_MC, EPI_F32, a, s));
     }
     if (dx) {  // dx = dG W_gate;  W_gate^T is [d,F]
@@ -332,6 +342,7 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
       GemmArgs a = {};
       a.A = dGb; a.lda = F; a.B = actT; a.ldb = ldT;
       a.M = F; a.N = d; a.K = ldT; a.K_mc = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
+      a.ksplit = dw_split; a.ws = c->dw_ws;
       HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_KC, EPI_F32, a, s));
     }
   } else {

@@ -74,8 +74,9 @@ struct Window {
 struct LoaderKC {
   uint32_t off[8];
   Window win;
-  __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int row0, int wave, int lane) {
-    win.set(p, (int64_t)rows * ld * 2);
+  // `skip`: elements by which p already points past the operand's first element (a K slice)
+  __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int row0, int wave, int lane, int skip) {
+    win.set(p, ((int64_t)rows * ld - skip) * 2);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = (wave * 8 + i) * 8 + (lane >> 3);
@@ -169,7 +170,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   const int wm = wave >> 1, wn = wave & 1;
   const int ntm = (p.M + BM - 1) / BM, ntn = (p.N + BN - 1) / BN;
   int tm, tn;
-  tile_of_block(blockIdx.x, gridDim.x, ntm, ntn, tm, tn);
+  if (EPI == EPI_F32 && p.ksplit > 1) {
+    // Split along K (weight gradients of narrow layers: few output tiles, long K): slice z of the
+    // K tiles, its product stored plainly to slice z of the partial buffer; a second kernel sums
+    // the slices in order.  The slice is expressed by moving the operands and shrinking K.
+    const int ntiles = ntm * ntn;
+    const int z = blockIdx.x / ntiles;
+    tile_of_block(blockIdx.x - z * ntiles, ntiles, ntm, ntn, tm, tn);
+    const int nk_all = (p.K + BK - 1) / BK;
+    const int per = (nk_all + p.ksplit - 1) / p.ksplit;
+    const int k0 = z * per * BK;
+    const int kmc = (p.K_mc > 0 ? p.K_mc : p.K) - k0;        // rows of a rows-contiguous operand left
+    int klen = p.K - k0;
+    if (klen > per * BK) klen = per * BK;
+    if (klen < 0) klen = 0;
+    p.A += LA == OP_KC ? (size_t)k0 : (size_t)k0 * p.lda;
+    p.B += LB == OP_KC ? (size_t)k0 : (size_t)k0 * p.ldb;
+    p.K = klen;
+    p.K_mc = kmc < 0 ? 0 : (kmc < klen ? kmc : klen);
+    p.kc_skip = k0;                                          // K-contiguous windows end k0 elements earlier
+    p.C = p.ws + (size_t)z * p.M * p.N;
+    p.accumulate = 0;
+  } else {
+    tile_of_block(blockIdx.x, gridDim.x, ntm, ntn, tm, tn);
+  }
   const int m0 = tm * BM, n0 = tn * BN;
 
   f32x16_t acc[4][4];
@@ -182,8 +206,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
 
   LoaderKC ka, kb_;
   LoaderMC ma, mb;
-  if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane); else ma.init(p.A, p.lda, p.M, p.K_mc > 0 ? p.K_mc : p.K, m0, tid);
-  if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane); else mb.init(p.B, p.ldb, p.N, p.K_mc > 0 ? p.K_mc : p.K, n0, tid);
+  if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane, p.kc_skip); else ma.init(p.A, p.lda, p.M, p.K_mc > 0 ? p.K_mc : p.K, m0, tid);
+  if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane, p.kc_skip); else mb.init(p.B, p.ldb, p.N, p.K_mc > 0 ? p.K_mc : p.K, n0, tid);
 
   // fragment addresses: per k-step one register per operand and stage, rows via immediates
   const int frow = lane & 31, fk = lane >> 5;
@@ -455,9 +479,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   }
 }
 
+// C[i] = (accumulate ? C[i] : 0) + (sum over the K slices, in slice order, of ws[z][i]); 4 elements per thread
+__global__ __launch_bounds__(256) void splitk_sum_f32_kernel(const float* __restrict__ ws, int ksplit, int64_t total,
+                                                             float* __restrict__ C, int accumulate) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= total) return;
+  f32x4_t s = *reinterpret_cast<const f32x4_t*>(ws + i);
+  for (int z = 1; z < ksplit; ++z) s += *reinterpret_cast<const f32x4_t*>(ws + (size_t)z * total + i);
+  if (accumulate) s += *reinterpret_cast<const f32x4_t*>(C + i);
+  *reinterpret_cast<f32x4_t*>(C + i) = s;
+}
+
 template <int LA, int LB, int EPI>
 hipError_t launch(stem_ctx* ctx, int kid, const GemmArgs& a, hipStream_t s) {
   const int ntm = (a.M + BM - 1) / BM, ntn = (a.N + BN - 1) / BN;
+  if (EPI == EPI_F32 && a.ksplit > 1) {
+    if (!a.ws || (a.M * (int64_t)a.N) % 4 != 0) return hipErrorInvalidValue;
+    {
+      ProfScope ps(ctx, kid, s);
+      hipLaunchKernelGGL((gemm_bf16_kernel<LA, LB, EPI>), dim3(ntm * ntn * a.ksplit), dim3(256), 0, s, a);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t total = (int64_t)a.M * a.N;
+    ProfScope ps(ctx, K_SPLITK_REDUCE, s);
+    hipLaunchKernelGGL(splitk_sum_f32_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s, a.ws, a.ksplit,
+                       total, static_cast<float*>(a.C), a.accumulate);
+    return hipGetLastError();
+  }
   ProfScope ps(ctx, kid, s);
   hipLaunchKernelGGL((gemm_bf16_kernel<LA, LB, EPI>), dim3(ntm * ntn), dim3(256), 0, s, a);
   return hipGetLastError();

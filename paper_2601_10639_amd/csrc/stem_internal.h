@@ -49,6 +49,8 @@ struct stem_ctx {
   void* WT_ws;           // [F*d] bf16: a weight matrix transposed (backward)
   void* actT_ws;         // [d, round_up(max_tokens, 64)] bf16: dy or x transposed (backward)
   float* splitk_ws;      // STEM_SPLITK_WS_BYTES: fp32 partial products of the few-row GEMMs
+  float* dw_ws;          // [dw_ksplit][d*F] fp32 partial weight gradients, when the layer is narrow
+  int dw_ksplit;         // K slices of the weight-gradient GEMMs (1 = no split)
   int32_t* sort_keys[2]; // [max_tokens]
   int32_t* sort_vals[2]; // [max_tokens]
   int32_t* sort_counts;  // [64 * waves]
@@ -128,8 +130,9 @@ struct GemmArgs {
   bf16_t* outdU;   // EPI_DH
   bf16_t* outdG;   // EPI_DH
   int32_t* flag;
-  float* ws;       // EPI_SPLITK: [ksplit][M][N] fp32
-  int ksplit;      // EPI_SPLITK: number of k slices
+  float* ws;       // split-K launches: [ksplit][M][N] fp32 partial products
+  int ksplit;      // number of k slices (few-row kernel: EPI_SPLITK; large kernel: EPI_F32 with ksplit > 1)
+  int kc_skip;     // set by the large kernel itself: elements a K slice starts after the operand's start
   int mt, nt;      // few-row kernel: tile counts and exact float reciprocals, filled in by the launcher
   float inv_mt, inv_per_z;
 };

@@ -90,9 +90,10 @@ def test_fp32_ragged_token_counts(T):
     _pipeline_case(s, T, seed=2)
 
 
-@pytest.mark.parametrize("T,d,F", [(600, 192, 576), (257, 64, 64), (1, 128, 320), (1100, 512, 256)])
+@pytest.mark.parametrize("T,d,F", [(600, 192, 576), (257, 64, 64), (1, 128, 320), (1100, 512, 256), (2100, 128, 320)])
 def test_bf16_several_tiles_and_ragged_tails(T, d, F):
-    # 256-wide tiles: these sizes give full tiles plus a ragged last tile in every dimension
+    # 256-wide tiles: these sizes give full tiles plus a ragged last tile in every dimension; the
+    # weight-gradient products of the last two are cut along K (2 slices; 4 slices of 9, 9, 9, 6 K tiles)
     s = inputs.StemShape("bf16-ragged", d, F, 1000, 1, T, "bf16")
     _pipeline_case(s, T, seed=3)
 
@@ -173,10 +174,11 @@ def test_whole_backward_is_bit_reproducible():
     ctx.close()
 
 
-def test_weight_gradient_accumulate_flag():
-    s = inputs.StemShape("acc", 64, 128, 100, 1, 90, "bf16")
-    inp = inputs.layer_inputs(s, 12, device=DEV, tokens=90)
-    ctx = Hn.make_ctx(s, 90)
+@pytest.mark.parametrize("T", [90, 1100])   # 1100 tokens: the K-sliced weight-gradient path
+def test_weight_gradient_accumulate_flag(T):
+    s = inputs.StemShape("acc", 64, 128, 100, 1, T, "bf16")
+    inp = inputs.layer_inputs(s, 12, device=DEV, tokens=T)
+    ctx = Hn.make_ctx(s, T)
     out = Hn.hip_forward_backward(ctx, inp)
     dWg = out["dW_gate"].clone()
     dWd = out["dW_down"].clone()
