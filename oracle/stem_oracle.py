@@ -2,8 +2,9 @@
 
 A plain, slow, fp64 numpy statement of what the layer computes, written from
 the paper's definition of the STEM layer (Method, "STEM", the equation
-y = W_d (SiLU(W_g x) * U[t])) and, for comparison pins, of the SwiGLU FFN
-(Background, first equation) and the additive variant (appendix "STEM-dagger").
+y = W_d (SiLU(W_g x) * U[t])) and of the two layers it is compared with: the
+SwiGLU FFN (Background, first equation) and the additive variant (appendix
+"STEM-dagger"), forward and backward (up_forward / up_backward).
 It shares no code with the HIP path and imports nothing from it.  Only
 tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import it;
 the product never routes through it.
@@ -19,8 +20,8 @@ intermediate is rounded, except where a function says so (bf16 shadow of the
 table, the residual stream of the stacked decode chain).
 
 Pin status: every function here is pinned by tests/test_oracle_pins.py
-(one-hot matmul forms, finite differences, the dense-SwiGLU invariant, torch's
-AdamW, closed forms, brute force).  Nothing is "parity unpinned".
+(one-hot matmul forms, finite differences, torch autograd, the dense-SwiGLU
+invariant, torch's AdamW, closed forms, brute force).  Nothing is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -123,6 +124,40 @@ def ffn_backward(dy, x, ids, W_gate, W_down, E):
     dW_down = dy.T @ f["h"]           # sum_i dy_i h_i^T
     dW_gate = dG.T @ x                # sum_i dg_i x_i^T
     return {"dx": dx, "dW_gate": dW_gate, "dW_down": dW_down, "dU": dU, "dG": dG}
+
+
+def up_forward(x, ids, W_gate, W_up, W_down, E=None):
+    """FFN with an up projection: dense SwiGLU (E is None; Background, first equation) or the
+    additive variant  y = W_d (SiLU(W_g x) * (W_u x + U[t]))  (appendix).
+
+    Returns (y [T,d], dict g, up, v = up (+ gathered rows), h [T,F]).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    g = x @ np.asarray(W_gate, dtype=np.float64).T
+    up = x @ np.asarray(W_up, dtype=np.float64).T
+    v = up if E is None else up + gather_rows(E, ids)
+    h = silu(g) * v
+    return h @ np.asarray(W_down, dtype=np.float64).T, {"g": g, "up": up, "v": v, "h": h}
+
+
+def up_backward(dy, x, ids, W_gate, W_up, W_down, E=None):
+    """Gradients of L = sum_i <y_i, dy_i> for up_forward (chain rule; not printed in the paper).
+
+    Returns dict: dx [T,d], dW_gate [F,d], dW_up [F,d], dW_down [d,F], dV [T,F] (gradient with
+    respect to v = W_u x + U[t]: it is both the up projection's output gradient and, in the
+    additive variant, the gradient of each token's gathered row), dG [T,F].
+    """
+    dy = np.asarray(dy, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    Wg = np.asarray(W_gate, dtype=np.float64)
+    Wu = np.asarray(W_up, dtype=np.float64)
+    Wd = np.asarray(W_down, dtype=np.float64)
+    _, f = up_forward(x, ids, Wg, Wu, Wd, E)
+    dh = dy @ Wd                       # W_d^T dy
+    dV = dh * silu(f["g"])             # h = SiLU(g) * v
+    dG = dh * f["v"] * silu_prime(f["g"])
+    dx = dG @ Wg + dV @ Wu             # x feeds both projections
+    return {"dx": dx, "dW_gate": dG.T @ x, "dW_up": dV.T @ x, "dW_down": dy.T @ f["h"], "dV": dV, "dG": dG}
 
 
 # ----------------------------------------------------------------------------

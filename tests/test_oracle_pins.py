@@ -194,6 +194,57 @@ def test_backward_against_torch_autograd():
 
 
 # -- embedding gradient ------------------------------------------------------
+def test_up_variants_forward_and_backward_against_torch_autograd():
+    # dense SwiGLU and the additive variant, written with torch's own silu / linear / embedding
+    rng = np.random.default_rng(21)
+    T, d, F, V = 9, 5, 7, 6
+    x, Wg, Wu, Wd = rng.normal(size=(T, d)), rng.normal(size=(F, d)), rng.normal(size=(F, d)), rng.normal(size=(d, F))
+    E, dy = rng.normal(size=(V, F)), rng.normal(size=(T, d))
+    ids = rng.integers(0, V, T)
+    for table in (None, E):
+        tx, tWg, tWu, tWd = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (x, Wg, Wu, Wd))
+        tE = torch.tensor(E, dtype=torch.float64, requires_grad=True)
+        v = torch.nn.functional.linear(tx, tWu)
+        if table is not None:
+            v = v + torch.nn.functional.embedding(torch.tensor(ids), tE)
+        y = torch.nn.functional.linear(torch.nn.functional.silu(torch.nn.functional.linear(tx, tWg)) * v, tWd)
+        (y * torch.tensor(dy)).sum().backward()
+        y_o, _ = O.up_forward(x, ids, Wg, Wu, Wd, table)
+        bw = O.up_backward(dy, x, ids, Wg, Wu, Wd, table)
+        np.testing.assert_allclose(y_o, y.detach().numpy(), rtol=1e-12, atol=1e-12)
+        for name, t in (("dx", tx), ("dW_gate", tWg), ("dW_up", tWu), ("dW_down", tWd)):
+            np.testing.assert_allclose(bw[name], t.grad.numpy(), rtol=1e-11, atol=1e-12, err_msg=name)
+        if table is not None:   # the table's gradient is the per-row sum of dV
+            np.testing.assert_allclose(O.embed_grad(ids, bw["dV"])["dE_rows"],
+                                       tE.grad.numpy()[np.unique(ids)], rtol=1e-11, atol=1e-12)
+
+
+def test_up_variants_reduce_to_the_stem_layer_and_to_each_other():
+    rng = np.random.default_rng(22)
+    T, d, F, V = 8, 4, 6, 5
+    x, Wg, Wu, Wd = rng.normal(size=(T, d)), rng.normal(size=(F, d)), rng.normal(size=(F, d)), rng.normal(size=(d, F))
+    E, dy = rng.normal(size=(V, F)), rng.normal(size=(T, d))
+    ids = rng.integers(0, V, T)
+    # W_up = 0: the STEM layer, forward and every gradient it has
+    y0, _ = O.up_forward(x, ids, Wg, np.zeros_like(Wu), Wd, E)
+    np.testing.assert_array_equal(y0, O.ffn_forward(x, ids, Wg, Wd, E)[0])
+    b0, bs = O.up_backward(dy, x, ids, Wg, np.zeros_like(Wu), Wd, E), O.ffn_backward(dy, x, ids, Wg, Wd, E)
+    for a, b in (("dx", "dx"), ("dW_gate", "dW_gate"), ("dW_down", "dW_down"), ("dV", "dU"), ("dG", "dG")):
+        np.testing.assert_allclose(b0[a], bs[b], rtol=1e-13, atol=1e-14)
+    # all-zero table: the dense FFN; and the published forward functions agree
+    y1, _ = O.up_forward(x, ids, Wg, Wu, Wd, np.zeros_like(E))
+    np.testing.assert_array_equal(y1, O.up_forward(x, ids, Wg, Wu, Wd, None)[0])
+    np.testing.assert_array_equal(y1, O.swiglu_forward(x, Wg, Wu, Wd))
+    np.testing.assert_array_equal(O.up_forward(x, ids, Wg, Wu, Wd, E)[0], O.stem_dagger_forward(x, ids, Wg, Wu, Wd, E))
+    # one finite difference through W_up (the term the STEM layer does not have)
+    h = 1e-6
+    Wp, Wm = Wu.copy(), Wu.copy()
+    Wp[2, 1] += h
+    Wm[2, 1] -= h
+    fd = ((O.up_forward(x, ids, Wg, Wp, Wd, E)[0] - O.up_forward(x, ids, Wg, Wm, Wd, E)[0]) * dy).sum() / (2 * h)
+    assert abs(fd - O.up_backward(dy, x, ids, Wg, Wu, Wd, E)["dW_up"][2, 1]) < 1e-7
+
+
 def test_embed_grad_is_onehot_transpose_matmul():
     x, ids, Wg, Wd, E, r = _tiny(seed=13)
     dU = O.ffn_backward(r, x, ids, Wg, Wd, E)["dU"]
