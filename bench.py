@@ -36,6 +36,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--ids", default="zipf", choices=["zipf", "uniform"], help="id distribution for C5")
+    ap.add_argument("--variant", default="stem", choices=["stem", "dense", "additive"],
+                    help="stem: the STEM layer (the headline); dense: SwiGLU FFN with an up projection and no table; "
+                         "additive: up projection plus table (C2, C3 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -89,13 +92,29 @@ def main() -> int:
     hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
     step_no = [0]
 
+    variant = args.variant
+    if variant != "stem":
+        if not bf16:
+            print("bench.py: --variant dense/additive needs a bf16 workload (C2, C3)", file=sys.stderr)
+            return 2
+        W_up = inputs.normal((F, d), 0.02, 3004, dt, dev)
+        Up = torch.empty(T, F, dtype=dt, device=dev)
+        dWu = torch.empty(F, d, dtype=torch.float32, device=dev)
+
     def step():
         step_no[0] += 1
-        L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, y, G, H)
-        L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, H, dx, dWg,
-                            dWd, dU)
-        L.stem_embed_grad(ctx, inp["ids"], dU, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, dE_rows)
-        L.stem_embed_sparse_adamw(ctx, uniq_ids, n_uniq, dE_rows, E, master, m, v, step=step_no[0], **hp)
+        if variant == "stem":
+            L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, y, G, H)
+            L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, H, dx, dWg,
+                                dWd, dU)
+        else:
+            tab, tid = (E, inp["ids"]) if variant == "additive" else (None, None)
+            L.stem_ffn_up_forward(ctx, inp["x"], tid, inp["W_gate"], W_up, inp["W_down"], tab, y, G, Up, H)
+            L.stem_ffn_up_backward(ctx, inp["dy"], inp["x"], tid, inp["W_gate"], W_up, inp["W_down"], tab, G, Up, H,
+                                   dx, dWg, dWu, dWd, dU)
+        if variant != "dense":
+            L.stem_embed_grad(ctx, inp["ids"], dU, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, dE_rows)
+            L.stem_embed_sparse_adamw(ctx, uniq_ids, n_uniq, dE_rows, E, master, m, v, step=step_no[0], **hp)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -114,7 +133,7 @@ def main() -> int:
     L.stem_sync_status(ctx)
     ms_per_step = elapsed / args.steps * 1e3
     tokens_per_s = T * args.steps / elapsed
-    U = int(n_uniq.item())
+    U = int(n_uniq.item()) if variant != "dense" else 0
 
     # Per-kernel durations: the same K steps again with HIP events around every launch, on the
     # stream the kernels run on.
@@ -138,7 +157,8 @@ def main() -> int:
         avg = ms / n
         k = {"avg_ms": round(avg, 5), "launches": n}
         if name.startswith("gemm_"):
-            k["tflops"] = round(gemm_flop / (avg * 1e-3) / 1e12, 2)
+            fl = gemm_flop * (2 if (name == "gemm_dx" and variant != "stem") else 1)   # dx spans both projections
+            k["tflops"] = round(fl / (avg * 1e-3) / 1e12, 2)
             k["frac_mfma_peak"] = round(k["tflops"] / peak_tf, 4)
         elif name in algo_bytes:
             k["gbs"] = round(algo_bytes[name] / (avg * 1e-3) / 1e9, 1)
@@ -153,6 +173,7 @@ def main() -> int:
     gemms = {k: v for k, v in kernels.items() if k.startswith("gemm_")}
     dom = max(gemms, key=lambda k: gemms[k]["avg_ms"] * gemms[k]["launches"])
     all_gemm_ms = sum(v["avg_ms"] for v in gemms.values())
+    n_gemm_units = 6 if variant == "stem" else 9   # products of 2*T*d*F FLOP each per step
     roofline = {
         "bound": "mfma" if bf16 else "alu",
         "kernel": dom,
@@ -161,12 +182,13 @@ def main() -> int:
         "unit": "TFLOP/s",
         "frac": round(gemms[dom]["tflops"] / peak_tf, 4),
         "traffic": traffic.get(dom),
-        "all_gemms_tflops": round(len(gemms) * gemm_flop / (all_gemm_ms * 1e-3) / 1e12, 2),
-        "all_gemms_frac": round(len(gemms) * gemm_flop / (all_gemm_ms * 1e-3) / 1e12 / peak_tf, 4),
+        "all_gemms_tflops": round(n_gemm_units * gemm_flop / (all_gemm_ms * 1e-3) / 1e12, 2),
+        "all_gemms_frac": round(n_gemm_units * gemm_flop / (all_gemm_ms * 1e-3) / 1e12 / peak_tf, 4),
     }
 
     out = {
-        "metric": "STEM FFN fwd+bwd tokens/s per layer",
+        "metric": "STEM FFN fwd+bwd tokens/s per layer" if variant == "stem" else
+                  ("dense SwiGLU FFN" if variant == "dense" else "additive-variant FFN") + " fwd+bwd tokens/s per layer",
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -179,12 +201,13 @@ def main() -> int:
         "dtype": shape.dtype,
         "data": "synthetic",
         "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T,
-                   "n_uniq": U, "ids": "Zipf(s=1.1)", "step": "fwd+bwd+embed_grad+sparse_adamw"},
+                   "n_uniq": U, "ids": "Zipf(s=1.1)", "variant": variant,
+                   "step": "fwd+bwd" if variant == "dense" else "fwd+bwd+embed_grad+sparse_adamw"},
         "roofline": roofline,
         "kernels": kernels,
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and variant == "stem":
         out["cpu_baseline"] = cpu_baseline(shape, inp, args.cpu_sample_tokens, hp)
     print(json.dumps(out))
     ctx.close()

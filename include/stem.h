@@ -143,6 +143,30 @@ stem_status stem_embed_sparse_adamw(stem_ctx* ctx, const int32_t* uniq_ids, cons
                                     int64_t max_rows, const float* dE_rows, void* E, float* master,
                                     float* m, float* v, const stem_adamw_hparams* hp, void* stream);
 
+/* ---- the layers STEM is compared with, through the same kernels (Background, SwiGLU FFN
+ *      equation; appendix, the additive variant) ------------------------------------ */
+
+/* y = (SiLU(x W_gate^T) * (x W_up^T + E[ids])) W_down^T;  with E == NULL (ids unused) the
+ * dense SwiGLU FFN y = (SiLU(x W_gate^T) * (x W_up^T)) W_down^T.  W_up [F,d]; everything else
+ * as in stem_ffn_forward.  save_G, save_Up, save_H: [T,F] bf16 or NULL; backward needs all
+ * three.  STEM_BF16 contexts only (STEM_ERR_UNSUPPORTED otherwise).  The first call on a
+ * context allocates one more [max_tokens,F] activation and one more [F,d] weight buffer. */
+stem_status stem_ffn_up_forward(stem_ctx* ctx, const void* x, const int32_t* ids, const void* W_gate,
+                                const void* W_up, const void* W_down, const void* E, int64_t E_rows,
+                                int64_t T, void* y, void* save_G, void* save_Up, void* save_H, void* stream);
+
+/* Gradients of the above for upstream dy [T,d].  With v = x W_up^T (+ E[ids]):
+ *   dH = dy W_down;  dV = dH * SiLU(G);  dG = dH * v * SiLU'(G);
+ *   dx = dG W_gate + dV W_up;  dW_gate = dG^T x;  dW_up = dV^T x;  dW_down = dy^T H.
+ * dV [T,F] bf16 is the gradient of the up projection's output and, when E is given, of
+ * each token's gathered row: stem_embed_grad(ids, dV) then yields the table's gradient.
+ * dx may be NULL.  dW_* fp32, overwritten unless accumulate != 0. */
+stem_status stem_ffn_up_backward(stem_ctx* ctx, const void* dy, const void* x, const int32_t* ids,
+                                 const void* W_gate, const void* W_up, const void* W_down, const void* E,
+                                 int64_t E_rows, const void* saved_G, const void* saved_Up,
+                                 const void* saved_H, int64_t T, void* dx, float* dW_gate, float* dW_up,
+                                 float* dW_down, void* dV, int accumulate, void* stream);
+
 /* ---- host-resident table (System Implementation: CPU offloading, asynchronous
  *      prefetch, token de-duplication) ------------------------------------------- */
 

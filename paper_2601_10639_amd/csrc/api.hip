@@ -20,7 +20,7 @@ const char* const kKernelNames[K_COUNT_] = {
     "gemm_gate_fused", "gemm_gate_plain", "gemm_down",    "gemm_dh_fused", "gemm_dx",      "gemm_dw_down",
     "gemm_dw_gate",    "silu_gather",     "dh_epilogue",  "sort_count",    "sort_scan",    "sort_scatter",
     "sort_fused",      "unique",          "seg_reduce",   "seg_combine",   "sparse_adamw", "row_copy",
-    "transpose",       "splitk_reduce"};
+    "transpose",       "splitk_reduce",   "gemm_up",      "gemm_dw_up"};
 
 stem_status fail(stem_ctx* c, stem_status st, const char* fmt, ...) {
   char* buf = c ? c->err : g_create_err;
@@ -71,6 +71,7 @@ void release(stem_ctx* c) {
   (void)hipDeviceSynchronize();
   (void)hipFree(c->H_ws); (void)hipFree(c->dG_ws); (void)hipFree(c->dH_ws);
   (void)hipFree(c->WT_ws); (void)hipFree(c->actT_ws); (void)hipFree(c->splitk_ws); (void)hipFree(c->dw_ws);
+  (void)hipFree(c->Up_ws); (void)hipFree(c->WT2_ws);
   for (int i = 0; i < 2; ++i) { (void)hipFree(c->sort_keys[i]); (void)hipFree(c->sort_vals[i]); }
   (void)hipFree(c->sort_counts); (void)hipFree(c->seg_of); (void)hipFree(c->seg_part);
   (void)hipFree(c->uniq_dev);
@@ -359,6 +360,139 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
     if (dx) HIP_TRY(c, stem_sgemm(c, K_GEMM_DX, dG, F, 1, Wg, 1, d, static_cast<float*>(dx), (int)T, d, F, 0, s));
     HIP_TRY(c, stem_sgemm(c, K_GEMM_DWGATE, dG, 1, F, static_cast<const float*>(x), 1, d, dW_gate, F, d, (int)T,
                           accumulate, s));
+  }
+  return STEM_OK;
+}
+
+// ---- dense SwiGLU FFN and the additive variant through the same kernels ---------------------------
+
+static stem_status up_scratch(stem_ctx* c) {
+  // these two entry points need one more [max_tokens, F] activation and one more transposed weight;
+  // they are allocated when the first such call arrives, not for every context
+  if (!c->Up_ws) {
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, hipMalloc(&c->Up_ws, std::max<size_t>((size_t)c->max_tokens * c->desc.d_ff * 2, 16)));
+    HIP_TRY(c, hipMalloc(&c->WT2_ws, (size_t)c->desc.d_ff * c->desc.d_model * 2));
+  }
+  return STEM_OK;
+}
+
+stem_status stem_ffn_up_forward(stem_ctx* c, const void* x, const int32_t* ids, const void* W_gate, const void* W_up,
+                                const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y, void* save_G,
+                                void* save_Up, void* save_H, void* stream) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (c->desc.dtype != STEM_BF16) return fail(c, STEM_ERR_UNSUPPORTED, "stem_ffn_up_forward: bf16 contexts only");
+  if (T == 0) return STEM_OK;
+  if (!x || !W_gate || !W_up || !W_down || !y || (E && !ids))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_up_forward: null pointer argument");
+  if (misaligned(x) || misaligned(W_gate) || misaligned(W_up) || misaligned(W_down) || misaligned(E) || misaligned(y) ||
+      misaligned(save_G) || misaligned(save_Up) || misaligned(save_H) || (reinterpret_cast<uintptr_t>(ids) & 3u))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_up_forward: pointers must be 16-byte aligned");
+  if (E && (E_rows < 1 || E_rows > INT32_MAX))
+    return fail(c, STEM_ERR_SHAPE, "stem_ffn_up_forward: E_rows = %lld", (long long)E_rows);
+  st = up_scratch(c);
+  if (st != STEM_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int d = c->desc.d_model, F = c->desc.d_ff;
+  void* H = save_H ? save_H : c->H_ws;
+  void* Up = save_Up ? save_Up : c->Up_ws;
+  GemmArgs u = {};   // Up = x W_up^T
+  u.A = static_cast<const bf16_t*>(x); u.lda = d;
+  u.B = static_cast<const bf16_t*>(W_up); u.ldb = d;
+  u.M = (int)T; u.N = F; u.K = d; u.C = Up; u.flag = c->flag;
+  HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_UP, OP_KC, OP_KC, EPI_BF16, u, s));
+  GemmArgs a = u;    // G = x W_gate^T;  H = SiLU(G) * (Up [+ E[ids]])
+  a.B = static_cast<const bf16_t*>(W_gate); a.C = nullptr;
+  a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows;
+  a.inUp = static_cast<const bf16_t*>(Up);
+  a.outG = static_cast<bf16_t*>(save_G); a.outH = static_cast<bf16_t*>(H);
+  HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_GATE, OP_KC, OP_KC, E ? EPI_GATE_UPE : EPI_GATE_UP, a, s));
+  GemmArgs b = {};   // y = H W_down^T
+  b.A = static_cast<const bf16_t*>(H); b.lda = F;
+  b.B = static_cast<const bf16_t*>(W_down); b.ldb = F;
+  b.M = (int)T; b.N = d; b.K = F; b.C = y; b.flag = c->flag;
+  HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, EPI_BF16, b, s));
+  return STEM_OK;
+}
+
+stem_status stem_ffn_up_backward(stem_ctx* c, const void* dy, const void* x, const int32_t* ids, const void* W_gate,
+                                 const void* W_up, const void* W_down, const void* E, int64_t E_rows,
+                                 const void* saved_G, const void* saved_Up, const void* saved_H, int64_t T, void* dx,
+                                 float* dW_gate, float* dW_up, float* dW_down, void* dV, int accumulate,
+                                 void* stream) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (c->desc.dtype != STEM_BF16) return fail(c, STEM_ERR_UNSUPPORTED, "stem_ffn_up_backward: bf16 contexts only");
+  if (!dW_gate || !dW_up || !dW_down)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_up_backward: null weight-gradient pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int d = c->desc.d_model, F = c->desc.d_ff;
+  if (T == 0) {
+    if (!accumulate) {
+      HIP_TRY(c, hipMemsetAsync(dW_gate, 0, (size_t)F * d * 4, s));
+      HIP_TRY(c, hipMemsetAsync(dW_up, 0, (size_t)F * d * 4, s));
+      HIP_TRY(c, hipMemsetAsync(dW_down, 0, (size_t)F * d * 4, s));
+    }
+    return STEM_OK;
+  }
+  if (!dy || !x || !W_gate || !W_up || !W_down || !saved_G || !saved_Up || !saved_H || !dV || (E && !ids))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_up_backward: null pointer argument");
+  if (misaligned(dy) || misaligned(x) || misaligned(W_gate) || misaligned(W_up) || misaligned(W_down) ||
+      misaligned(E) || misaligned(saved_G) || misaligned(saved_Up) || misaligned(saved_H) || misaligned(dx) ||
+      misaligned(dW_gate) || misaligned(dW_up) || misaligned(dW_down) || misaligned(dV) ||
+      (reinterpret_cast<uintptr_t>(ids) & 3u))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_up_backward: pointers must be 16-byte aligned");
+  if (E && (E_rows < 1 || E_rows > INT32_MAX))
+    return fail(c, STEM_ERR_SHAPE, "stem_ffn_up_backward: E_rows = %lld", (long long)E_rows);
+  st = up_scratch(c);
+  if (st != STEM_OK) return st;
+
+  const bf16_t* dyb = static_cast<const bf16_t*>(dy);
+  bf16_t* dGb = static_cast<bf16_t*>(c->dG_ws);
+  bf16_t* dVb = static_cast<bf16_t*>(dV);
+  bf16_t* WT = static_cast<bf16_t*>(c->WT_ws);
+  bf16_t* WT2 = static_cast<bf16_t*>(c->WT2_ws);
+  bf16_t* actT = static_cast<bf16_t*>(c->actT_ws);
+  const int ldT = (int)((T + 63) / 64 * 64);
+  int dw_split = c->dw_ksplit;
+  while (dw_split > 1 && ldT / 64 / dw_split < 8) dw_split /= 2;
+  {  // dH = dy W_down, fused into dV = dH * SiLU(G) and dG = dH * (Up [+ E[ids]]) * SiLU'(G)
+    HIP_TRY(c, stem_transpose_bf16(c, W_down, d, F, WT, d, s));
+    GemmArgs a = {};
+    a.A = dyb; a.lda = d; a.B = WT; a.ldb = d;
+    a.M = (int)T; a.N = F; a.K = d;
+    a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows; a.flag = c->flag;
+    a.inG = static_cast<const bf16_t*>(saved_G); a.inUp = static_cast<const bf16_t*>(saved_Up);
+    a.outdU = dVb; a.outdG = dGb;
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_KC, E ? EPI_DH_UPE : EPI_DH_UP, a, s));
+  }
+  {  // dW_down[d,F] = dy^T H
+    HIP_TRY(c, stem_transpose_bf16(c, dy, (int)T, d, actT, ldT, s));
+    GemmArgs a = {};
+    a.A = actT; a.lda = ldT; a.B = static_cast<const bf16_t*>(saved_H); a.ldb = F;
+    a.M = d; a.N = F; a.K = ldT; a.K_mc = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
+    a.ksplit = dw_split; a.ws = c->dw_ws;
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_KC, OP_MC, EPI_F32, a, s));
+  }
+  if (dx) {  // dx = dG W_gate + dV W_up: one product over the concatenated K range
+    HIP_TRY(c, stem_transpose_bf16(c, W_gate, F, d, WT, F, s));
+    HIP_TRY(c, stem_transpose_bf16(c, W_up, F, d, WT2, F, s));
+    GemmArgs a = {};
+    a.A = dGb; a.lda = F; a.B = WT; a.ldb = F;
+    a.A2 = dVb; a.B2 = WT2; a.K2 = F;
+    a.M = (int)T; a.N = d; a.K = F; a.C = dx; a.flag = c->flag;
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_KC, EPI_BF16, a, s));
+  }
+  {  // dW_gate[F,d] = dG^T x and dW_up[F,d] = dV^T x
+    HIP_TRY(c, stem_transpose_bf16(c, x, (int)T, d, actT, ldT, s));
+    GemmArgs a = {};
+    a.A = dGb; a.lda = F; a.B = actT; a.ldb = ldT;
+    a.M = F; a.N = d; a.K = ldT; a.K_mc = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
+    a.ksplit = dw_split; a.ws = c->dw_ws;
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_KC, EPI_F32, a, s));
+    a.A = dVb; a.C = dW_up;
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWUP, OP_MC, OP_KC, EPI_F32, a, s));
   }
   return STEM_OK;
 }

@@ -275,12 +275,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       mb.commit(q, next_stage + TILE_BYTES, tid);
     }
   };
+  // A second operand pair (A2, B2, K2; both K-contiguous, same leading dimensions) continues the
+  // sum: after the K tiles of the first pair the windows move to the second.
+  const int nk1 = (p.K + BK - 1) / BK;
+  int tiles_to_switch = (LA == OP_KC && LB == OP_KC && p.A2) ? nk1 : -1;
   auto advance = [&]() {
+    if (LA == OP_KC && LB == OP_KC && --tiles_to_switch == 0) {
+      ka.win.set(p.A2, (int64_t)p.M * p.lda * 2);
+      kb_.win.set(p.B2, (int64_t)p.N * p.ldb * 2);
+      return;
+    }
     if (LA == OP_KC) ka.next_tile(); else ma.next_tile();
     if (LB == OP_KC) kb_.next_tile(); else mb.next_tile();
   };
 
-  const int nk = (p.K + BK - 1) / BK;
+  const int nk = nk1 + ((LA == OP_KC && LB == OP_KC && p.A2) ? (p.K2 + BK - 1) / BK : 0);
   // ---- prologue: tile 0 into stage 0 -------------------------------------------------
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
@@ -385,25 +394,33 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   const int n = n0 + wn * 128 + scol;
   const bool n_ok = n < p.N;
   const int n_ld = n_ok ? n : 0;              // in-bounds column for the prefetching loads
-  constexpr bool FUSED = (EPI == EPI_GATE || EPI == EPI_DH);
+  constexpr bool GATE_LIKE = (EPI == EPI_GATE || EPI == EPI_GATE_UP || EPI == EPI_GATE_UPE);
+  constexpr bool DH_LIKE = (EPI == EPI_DH || EPI == EPI_DH_UP || EPI == EPI_DH_UPE);
+  constexpr bool USE_E = (EPI == EPI_GATE || EPI == EPI_DH || EPI == EPI_GATE_UPE || EPI == EPI_DH_UPE);
+  constexpr bool USE_UP = (EPI == EPI_GATE_UP || EPI == EPI_GATE_UPE || EPI == EPI_DH_UP || EPI == EPI_DH_UPE);
+  constexpr bool FUSED = GATE_LIKE || DH_LIKE;
 
   // Everything the element-wise part needs from memory is requested one 32-row block ahead
   // (8 rows per lane and block), so the gathered table rows arrive while the previous block
   // is being staged and stored.
-  uint4 ev[2][8], gv[2][8];
+  // ev: gathered table row, uv: up-projection row (dense and additive variants), gv: saved G row
+  uint4 ev[2][8], gv[2][8], uv[2][8];
   auto prefetch = [&](int i, int buf) __attribute__((always_inline)) {
     if (!FUSED) return;
 #pragma unroll
     for (int pass = 0; pass < 8; ++pass) {
       const int m = m0 + wm * 128 + i * 32 + pass * 4 + srow;
       const int mc = m < p.M ? m : p.M - 1;
-      int id = p.ids[mc];
-      if ((unsigned)id >= (unsigned)p.E_rows) {
-        *p.flag = 1;
-        id = id < 0 ? 0 : p.E_rows - 1;
+      if (USE_E) {
+        int id = p.ids[mc];
+        if ((unsigned)id >= (unsigned)p.E_rows) {
+          *p.flag = 1;
+          id = id < 0 ? 0 : p.E_rows - 1;
+        }
+        ev[buf][pass] = *reinterpret_cast<const uint4*>(p.E + (size_t)id * p.N + n_ld);
       }
-      ev[buf][pass] = *reinterpret_cast<const uint4*>(p.E + (size_t)id * p.N + n_ld);
-      if (EPI == EPI_DH) gv[buf][pass] = *reinterpret_cast<const uint4*>(p.inG + (size_t)mc * p.N + n_ld);
+      if (USE_UP) uv[buf][pass] = *reinterpret_cast<const uint4*>(p.inUp + (size_t)mc * p.N + n_ld);
+      if (DH_LIKE) gv[buf][pass] = *reinterpret_cast<const uint4*>(p.inG + (size_t)mc * p.N + n_ld);
     }
   };
   prefetch(0, 0);
@@ -447,9 +464,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
           dst[1] = v1;
         }
       } else {
+        // e: what SiLU(G) is multiplied by: the gathered row, the up projection, or their sum
         float e[8];
-        unpack8(ev[i & 1][pass], e);
-        if (EPI == EPI_GATE) {
+        if (USE_E) unpack8(ev[i & 1][pass], e);
+        if (USE_UP) {
+          float u[8];
+          unpack8(uv[i & 1][pass], u);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) e[q] = USE_E ? e[q] + u[q] : u[q];
+        }
+        if (GATE_LIKE) {
           float h[8];
 #pragma unroll
           for (int q = 0; q < 8; ++q) h[q] = c[q] * sigmoidf_fast(c[q]) * e[q];
@@ -457,7 +481,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
             if (p.outG) *reinterpret_cast<uint4*>(p.outG + o) = pack8(c);
             *reinterpret_cast<uint4*>(p.outH + o) = pack8(h);
           }
-        } else {  // EPI_DH
+        } else {  // dH product
           float gz[8], du[8], dg[8];
           unpack8(gv[i & 1][pass], gz);
 #pragma unroll
@@ -526,6 +550,10 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
     if (epi == EPI_BF16) return launch<OP_KC, OP_KC, EPI_BF16>(ctx, kid, a, s);
     if (epi == EPI_GATE) return launch<OP_KC, OP_KC, EPI_GATE>(ctx, kid, a, s);
     if (epi == EPI_DH) return launch<OP_KC, OP_KC, EPI_DH>(ctx, kid, a, s);
+    if (epi == EPI_GATE_UP) return launch<OP_KC, OP_KC, EPI_GATE_UP>(ctx, kid, a, s);
+    if (epi == EPI_GATE_UPE) return launch<OP_KC, OP_KC, EPI_GATE_UPE>(ctx, kid, a, s);
+    if (epi == EPI_DH_UP) return launch<OP_KC, OP_KC, EPI_DH_UP>(ctx, kid, a, s);
+    if (epi == EPI_DH_UPE) return launch<OP_KC, OP_KC, EPI_DH_UPE>(ctx, kid, a, s);
   } else if (la == OP_KC && lb == OP_MC) {
     if (epi == EPI_BF16) return launch<OP_KC, OP_MC, EPI_BF16>(ctx, kid, a, s);
     if (epi == EPI_DH) return launch<OP_KC, OP_MC, EPI_DH>(ctx, kid, a, s);

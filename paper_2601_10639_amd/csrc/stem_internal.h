@@ -28,7 +28,9 @@ enum StemKernelId {
   K_ADAMW,
   K_ROW_COPY,        // host-resident rows -> compact device table
   K_TRANSPOSE,       // bf16 operand transposes ahead of the backward GEMMs
-  K_SPLITK_REDUCE,   // sum of the split-K partial products of a few-row GEMM
+  K_SPLITK_REDUCE,   // sum of split-K partial products
+  K_GEMM_UP,         // Up = X Wu^T (dense SwiGLU and the additive variant)
+  K_GEMM_DWUP,       // dWu = dV^T X
   K_COUNT_
 };
 
@@ -48,6 +50,8 @@ struct stem_ctx {
   void* dH_ws;           // [max_tokens, F] fp32, STEM_F32 only
   void* WT_ws;           // [F*d] bf16: a weight matrix transposed (backward)
   void* actT_ws;         // [d, round_up(max_tokens, 64)] bf16: dy or x transposed (backward)
+  void* Up_ws;           // [max_tokens, F] bf16, allocated by the first stem_ffn_up_* call
+  void* WT2_ws;          // [F*d] bf16, second transposed weight, ditto
   float* splitk_ws;      // STEM_SPLITK_WS_BYTES: fp32 partial products of the few-row GEMMs
   float* dw_ws;          // [dw_ksplit][d*F] fp32 partial weight gradients, when the layer is narrow
   int dw_ksplit;         // K slices of the weight-gradient GEMMs (1 = no split)
@@ -110,7 +114,10 @@ enum GemmEpilogue {
   EPI_F32,      // C -> fp32 [M,N], optional +=
   EPI_GATE,     // G (optional) and H = SiLU(C) * E[ids[m], n], both bf16
   EPI_DH,       // dU = C * SiLU(G), dG = C * E[ids[m], n] * SiLU'(G), both bf16
-  EPI_SPLITK    // few-row kernel only: fp32 partial products per k slice, summed into bf16 C
+  EPI_SPLITK,   // few-row kernel only: fp32 partial products per k slice, summed into bf16 C
+  // dense SwiGLU (UP) and the additive variant (UPE): SiLU(C) is multiplied by Up or Up + E[ids]
+  EPI_GATE_UP, EPI_GATE_UPE,
+  EPI_DH_UP, EPI_DH_UPE
 };
 
 struct GemmArgs {
@@ -126,6 +133,10 @@ struct GemmArgs {
   int E_rows;
   bf16_t* outG;    // EPI_GATE: may be null
   bf16_t* outH;    // EPI_GATE
+  const bf16_t* inUp; // *_UP, *_UPE: the up projection x W_up^T, [M,N] bf16
+  const bf16_t* A2;  // optional second operand pair of a (KC,KC) product: C = A B^T + A2 B2^T
+  const bf16_t* B2;
+  int K2;
   const bf16_t* inG; // EPI_DH
   bf16_t* outdU;   // EPI_DH
   bf16_t* outdG;   // EPI_DH

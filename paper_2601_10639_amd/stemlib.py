@@ -21,7 +21,8 @@ STEM_F32, STEM_BF16 = 0, 1
 
 SYMBOLS = [
     "stem_create", "stem_destroy", "stem_last_error", "stem_status_string", "stem_sync_status",
-    "stem_ffn_forward", "stem_ffn_backward", "stem_embed_grad", "stem_embed_sparse_adamw",
+    "stem_ffn_forward", "stem_ffn_backward", "stem_ffn_up_forward", "stem_ffn_up_backward",
+    "stem_embed_grad", "stem_embed_sparse_adamw",
     "stem_prefetch_rows", "stem_profile_enable", "stem_profile_kernels", "stem_profile_read",
     "stem_profile_reset",
 ]
@@ -68,6 +69,11 @@ def lib() -> ctypes.CDLL:
         L.stem_ffn_forward.restype = i32
         L.stem_ffn_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp, i32, vp]
         L.stem_ffn_backward.restype = i32
+        L.stem_ffn_up_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp]
+        L.stem_ffn_up_forward.restype = i32
+        L.stem_ffn_up_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp, i64, vp, vp, vp, vp, vp,
+                                           i32, vp]
+        L.stem_ffn_up_backward.restype = i32
         L.stem_embed_grad.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
         L.stem_embed_grad.restype = i32
         L.stem_embed_sparse_adamw.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp,
@@ -185,6 +191,37 @@ def stem_ffn_backward(ctx: StemCtx, dy, x, ids, W_gate, W_down, E, saved_G, save
                                  _ptr(dW_down, torch.float32, name="dW_down"), _ptr(dU, dt, name="dU"),
                                  1 if accumulate else 0, _stream(stream))
     _check(ctx, st, "stem_ffn_backward")
+
+
+def stem_ffn_up_forward(ctx: StemCtx, x, ids, W_gate, W_up, W_down, E, y, save_G=None, save_Up=None, save_H=None,
+                        stream=None, E_rows=None, T=None):
+    """E (and ids) may be None: the dense SwiGLU FFN."""
+    dt = ctx.torch_dtype
+    T = x.shape[0] if T is None else T
+    E_rows = (E.shape[0] if E is not None else 0) if E_rows is None else E_rows
+    st = lib().stem_ffn_up_forward(ctx.handle, _ptr(x, dt, name="x"), _ptr(ids, torch.int32, name="ids"),
+                                   _ptr(W_gate, dt, name="W_gate"), _ptr(W_up, dt, name="W_up"),
+                                   _ptr(W_down, dt, name="W_down"), _ptr(E, dt, name="E"), E_rows, T,
+                                   _ptr(y, dt, name="y"), _ptr(save_G, dt, name="save_G"),
+                                   _ptr(save_Up, dt, name="save_Up"), _ptr(save_H, dt, name="save_H"), _stream(stream))
+    _check(ctx, st, "stem_ffn_up_forward")
+
+
+def stem_ffn_up_backward(ctx: StemCtx, dy, x, ids, W_gate, W_up, W_down, E, saved_G, saved_Up, saved_H, dx, dW_gate,
+                         dW_up, dW_down, dV, accumulate: bool = False, stream=None, E_rows=None, T=None):
+    dt = ctx.torch_dtype
+    f32 = torch.float32
+    T = dy.shape[0] if T is None else T
+    E_rows = (E.shape[0] if E is not None else 0) if E_rows is None else E_rows
+    st = lib().stem_ffn_up_backward(ctx.handle, _ptr(dy, dt, name="dy"), _ptr(x, dt, name="x"),
+                                    _ptr(ids, torch.int32, name="ids"), _ptr(W_gate, dt, name="W_gate"),
+                                    _ptr(W_up, dt, name="W_up"), _ptr(W_down, dt, name="W_down"),
+                                    _ptr(E, dt, name="E"), E_rows, _ptr(saved_G, dt, name="saved_G"),
+                                    _ptr(saved_Up, dt, name="saved_Up"), _ptr(saved_H, dt, name="saved_H"), T,
+                                    _ptr(dx, dt, name="dx"), _ptr(dW_gate, f32, name="dW_gate"),
+                                    _ptr(dW_up, f32, name="dW_up"), _ptr(dW_down, f32, name="dW_down"),
+                                    _ptr(dV, dt, name="dV"), 1 if accumulate else 0, _stream(stream))
+    _check(ctx, st, "stem_ffn_up_backward")
 
 
 def stem_embed_grad(ctx: StemCtx, ids, dU, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, dE_rows, stream=None,

@@ -135,6 +135,50 @@ def test_bf16_few_row_forward(T, d, F):
     ctx.close()
 
 
+@pytest.mark.parametrize("with_table", [False, True])
+@pytest.mark.parametrize("T,d,F", [(700, 192, 576), (1100, 128, 320), (300, 256, 256)])
+def test_bf16_dense_swiglu_and_additive_variant(T, d, F, with_table):
+    """The layers the STEM layer is compared with, through the same GEMM kernels: up projection,
+    epilogues that multiply SiLU(G) by Up or Up + E[ids], dx over the concatenated K range."""
+    V = 300
+    s = inputs.StemShape("up-variants", d, F, V, 1, T, "bf16")
+    inp = inputs.layer_inputs(s, seed=17, device=DEV, tokens=T)
+    Wu = inputs.normal((F, d), 0.02, 18, torch.bfloat16, DEV)
+    E = inp["E"] if with_table else None
+    ids = inp["ids"] if with_table else None
+    ctx = Hn.make_ctx(s, T)
+    bf = torch.bfloat16
+    y = torch.empty(T, d, dtype=bf, device=DEV)
+    G, Up, H, dV = (torch.empty(T, F, dtype=bf, device=DEV) for _ in range(4))
+    dx = torch.empty(T, d, dtype=bf, device=DEV)
+    dWg, dWu = (torch.empty(F, d, dtype=torch.float32, device=DEV) for _ in range(2))
+    dWd = torch.empty(d, F, dtype=torch.float32, device=DEV)
+    L.stem_ffn_up_forward(ctx, inp["x"], ids, inp["W_gate"], Wu, inp["W_down"], E, y, G, Up, H)
+    L.stem_ffn_up_backward(ctx, inp["dy"], inp["x"], ids, inp["W_gate"], Wu, inp["W_down"], E, G, Up, H, dx, dWg, dWu,
+                           dWd, dV)
+    y2 = torch.empty_like(y)
+    L.stem_ffn_up_forward(ctx, inp["x"], ids, inp["W_gate"], Wu, inp["W_down"], E, y2)   # nothing saved
+    L.stem_sync_status(ctx)
+    f64 = {k: inputs.to_f64(v) for k, v in inp.items() if k != "ids"}
+    ids_np = inp["ids"].cpu().numpy()
+    E64 = f64["E"] if with_table else None
+    ref, fw = O.up_forward(f64["x"], ids_np, f64["W_gate"], inputs.to_f64(Wu), f64["W_down"], E64)
+    bw = O.up_backward(f64["dy"], f64["x"], ids_np, f64["W_gate"], inputs.to_f64(Wu), f64["W_down"], E64)
+    errs = {"y": Hn.max_rel(y.float().cpu(), ref), "G": Hn.max_rel(G.float().cpu(), fw["g"]),
+            "Up": Hn.max_rel(Up.float().cpu(), fw["up"]), "H": Hn.max_rel(H.float().cpu(), fw["h"]),
+            "dx": Hn.max_rel(dx.float().cpu(), bw["dx"]), "dV": Hn.max_rel(dV.float().cpu(), bw["dV"]),
+            "dW_gate": Hn.max_rel(dWg.cpu(), bw["dW_gate"]), "dW_up": Hn.max_rel(dWu.cpu(), bw["dW_up"]),
+            "dW_down": Hn.max_rel(dWd.cpu(), bw["dW_down"])}
+    bad = {k: v for k, v in errs.items() if not v <= Hn.TOL["bf16"]}
+    assert not bad, (bad, errs)
+    assert torch.equal(y, y2)
+    if with_table:   # the table's gradient comes from dV exactly as it comes from dU in the STEM layer
+        eg = Hn.hip_embed_grad(ctx, inp["ids"], dV, V)
+        U = Hn.check_integers(eg, ids_np)
+        assert Hn.max_rel(eg["dE_rows"][:U].cpu(), O.embed_grad(ids_np, bw["dV"])["dE_rows"]) <= Hn.TOL["bf16"]
+    ctx.close()
+
+
 @pytest.mark.parametrize("T,V", [(1, 1), (2, 2), (64, 5), (4096, 50304), (4097, 128256), (16384, 128256),
                                  (65536, 128256), (70001, 64), (5000, (1 << 20) + 3)])
 def test_sort_unique_offsets_bit_exact(T, V):
