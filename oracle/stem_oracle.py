@@ -274,6 +274,61 @@ def dedup_remap(ids):
     return np.asarray(uniq, dtype=np.int32), remap
 
 
+class LfuRowCache:
+    """Least-frequently-used cache of table rows kept on the device in host-resident mode
+    (System Implementation: the hot rows stay in GPU memory, only misses are prefetched).
+
+    The paper names the policy (LFU) and a hit rate, not its details; the reading taken:
+    * freq[id] counts every token occurrence of id seen so far;
+    * a batch's distinct ids are hits (row already in a cache slot) or misses; misses are
+      numbered in order of first use and their rows go to the staging area behind the cache:
+      remap[i] = slot (hit) or n_slots + miss number (miss);
+    * after the batch, misses are offered to the cache in order (freq descending, id ascending):
+      a free slot (lowest index first) is taken; otherwise the coldest cached row that this
+      batch did not use (freq ascending, id ascending) is replaced if the candidate's freq is
+      strictly larger; the first candidate that fails ends the update.
+    """
+
+    def __init__(self, vocab: int, n_slots: int):
+        self.n_slots = int(n_slots)
+        self.freq = np.zeros(int(vocab), dtype=np.int64)
+        self.id_in_slot = [-1] * self.n_slots
+        self.slot_of = {}
+
+    def step(self, ids):
+        """Returns (remap [T] int32, misses [n_miss] int32 in copy order, installs list of
+        (id, slot, miss number))."""
+        ids = [int(t) for t in np.asarray(ids, dtype=np.int64)]
+        for t in ids:
+            self.freq[t] += 1
+        miss_no, misses, used = {}, [], set()
+        remap = np.empty(len(ids), dtype=np.int32)
+        for i, t in enumerate(ids):
+            used.add(t)
+            if t in self.slot_of:
+                remap[i] = self.slot_of[t]
+            else:
+                if t not in miss_no:
+                    miss_no[t] = len(misses)
+                    misses.append(t)
+                remap[i] = self.n_slots + miss_no[t]
+        free = [s for s in range(self.n_slots) if self.id_in_slot[s] < 0]
+        cold = sorted((int(self.freq[t]), t) for t in self.slot_of if t not in used)
+        installs = []
+        for t in sorted(misses, key=lambda t: (-int(self.freq[t]), t)):
+            if free:
+                slot = free.pop(0)
+            elif cold and int(self.freq[t]) > cold[0][0]:
+                _, victim = cold.pop(0)
+                slot = self.slot_of.pop(victim)
+            else:
+                break
+            self.id_in_slot[slot] = t
+            self.slot_of[t] = slot
+            installs.append((t, slot, miss_no[t]))
+        return remap, np.asarray(misses, dtype=np.int32), installs
+
+
 # ----------------------------------------------------------------------------
 # stacked decode chain (several STEM layers joined by a residual stream)
 # ----------------------------------------------------------------------------

@@ -51,12 +51,15 @@ def torch_dtype(name: str) -> torch.dtype:
     return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
 
 
-def zipf_ids(n: int, vocab: int, seed: int, s: float = 1.1, permute: bool = True) -> np.ndarray:
+def zipf_ids(n: int, vocab: int, seed: int, s: float = 1.1, permute: bool = True,
+             perm_seed: int | None = None) -> np.ndarray:
     """n token ids in [0, vocab) with P(rank k) proportional to k**-s, k = 1..vocab.
 
     Sampling is inverse-CDF on an fp64 cumulative table.  With `permute` the
     rank -> id map is a seeded permutation, so frequent rows are scattered
     through the table as in a real vocabulary; otherwise rank k maps to id k-1.
+    Successive batches of one token stream share `perm_seed` (the vocabulary)
+    and differ in `seed` (the draws); by default each seed has its own vocabulary.
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     w = np.arange(1, vocab + 1, dtype=np.float64) ** (-s)
@@ -65,7 +68,7 @@ def zipf_ids(n: int, vocab: int, seed: int, s: float = 1.1, permute: bool = True
     u = rng.random(n)
     ranks = np.minimum(np.searchsorted(cdf, u, side="right"), vocab - 1)
     if permute:
-        pi = np.random.Generator(np.random.PCG64(seed + 7919)).permutation(vocab)
+        pi = np.random.Generator(np.random.PCG64(seed + 7919 if perm_seed is None else perm_seed)).permutation(vocab)
         ranks = pi[ranks]
     return ranks.astype(np.int32)
 

@@ -374,6 +374,43 @@ def test_dedup_remap_matches_numpy_unique():
     np.testing.assert_array_equal(uniq[remap], ids)
 
 
+def test_lfu_row_cache_serves_right_rows_and_keeps_the_most_frequent():
+    # simulate the device buffer [cache slots | staging] and check every token finds its row;
+    # check the LFU property after every batch; check the hit rate on a Zipf stream
+    V, F, n_slots, T = 400, 3, 40, 300
+    rng = np.random.default_rng(31)
+    table = rng.normal(size=(V, F))
+    dev = np.full((n_slots + T, F), np.nan)
+    cache = O.LfuRowCache(V, n_slots)
+    hit_tokens = total = 0
+    for b in range(12):
+        ids = inputs.zipf_ids(T, V, seed=100 + b, perm_seed=5)
+        cached_before = dict(cache.slot_of)
+        remap, misses, installs = cache.step(ids)
+        dev[n_slots:n_slots + len(misses)] = table[misses]          # the copy of the missed rows
+        np.testing.assert_array_equal(dev[remap], table[ids])        # every token reads its own row
+        assert len(set(misses.tolist())) == len(misses) and not set(misses.tolist()) & set(cached_before)
+        first_use = [t for k, t in enumerate(ids.tolist()) if t not in ids[:k].tolist() and t not in cached_before]
+        assert misses.tolist() == first_use                          # copy order = order of first use
+        for t, slot, j in installs:                                  # promotion from the staging area
+            assert misses[j] == t
+            dev[slot] = dev[n_slots + j]
+        for t, slot in cache.slot_of.items():
+            assert cache.id_in_slot[slot] == t
+            np.testing.assert_array_equal(dev[slot], table[t])
+        # LFU: no id of this batch left outside is more frequent than a cached row the batch did not use
+        outside = [t for t in misses.tolist() if t not in cache.slot_of]
+        cold = [t for t in cache.slot_of if t not in set(ids.tolist())]
+        if outside and cold:
+            assert max(cache.freq[t] for t in outside) <= min(cache.freq[t] for t in cold)
+        if b >= 6:
+            hit_tokens += sum(1 for t in ids.tolist() if t in cached_before)
+            total += T
+    assert sum(s >= 0 for s in cache.id_in_slot) == n_slots
+    # the 40 hottest of 400 Zipf(1.1) ids carry about 62 % of the token mass
+    assert 0.5 < hit_tokens / total < 0.75, hit_tokens / total
+
+
 def test_decode_chain_composes_layers_with_rounded_residual():
     rng = np.random.default_rng(21)
     T, d, F, V = 4, 8, 16, 5
