@@ -36,6 +36,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--ids", default="zipf", choices=["zipf", "uniform"], help="id distribution for C5")
+    ap.add_argument("--cache-slots", type=int, default=0,
+                    help="C5: device-resident LFU cache of this many rows (0 = none); ten batches warm it first")
     ap.add_argument("--variant", default="stem", choices=["stem", "dense", "additive"],
                     help="stem: the STEM layer (the headline); dense: SwiGLU FFN with an up projection and no table; "
                          "additive: up projection plus table (C2, C3 only)")
@@ -324,9 +326,27 @@ def bench_host_table(args, shape, dev):
     ids_dev = ids_host.to(dev)
     E_dev = E_host.to(dev)
     dedup_ms = []
+    NS = args.cache_slots
+    miss_rows, uniq_rows = [U], [U]
+    if NS > 0:
+        # one token stream: batches share the vocabulary (which ids are frequent) and differ in the draws
+        stream = [torch.from_numpy(inputs.zipf_ids(T, V, seed=500 + b, perm_seed=77) if args.ids == "zipf"
+                                   else inputs.uniform_ids(T, V, seed=500 + b))
+                  for b in range(max(args.warmup, 10) + args.steps + 3)]   # no batch is seen twice
+        E_cached = torch.empty(NS + T, F, dtype=torch.bfloat16, device=dev)
+        L.stem_cache_init(ctx, NS)
+        turn = [0]
 
     def step():
         t0 = time.perf_counter()
+        if NS > 0:
+            ids_b = stream[turn[0] % len(stream)]
+            turn[0] += 1
+            n, nm, ev = L.stem_prefetch_rows_cached(ctx, E_host, ids_b, E_cached, NS, remap)
+            miss_rows[0], uniq_rows[0] = nm, n
+            dedup_ms.append((time.perf_counter() - t0) * 1e3)
+            L.stem_ffn_forward(ctx, x, remap, Wg, Wd, E_cached, y, wait_event=ev)
+            return
         n, ev = L.stem_prefetch_rows(ctx, E_host, ids_host, E_compact, remap)
         dedup_ms.append((time.perf_counter() - t0) * 1e3)
         L.stem_ffn_forward(ctx, x, remap, Wg, Wd, E_compact, y, wait_event=ev, E_rows=n)
@@ -335,14 +355,18 @@ def bench_host_table(args, shape, dev):
         L.stem_ffn_forward(ctx, x, ids_dev, Wg, Wd, E_dev, y)
 
     steps, warm = args.steps, args.warmup
+    if NS > 0:
+        warm = max(warm, 10)   # the cache fills and settles
     med, p10, p90 = _median_ms(step, steps, warm)
     del dedup_ms[:warm]
     res_med, _, _ = _median_ms(step_resident, steps, warm)
     L.stem_sync_status(ctx)
     # the link itself: one contiguous pinned copy of as many bytes as the rows
-    nbytes = U * F * 2
-    flat = E_host.view(-1)[: U * F]
-    dst = torch.empty(U * F, dtype=torch.bfloat16, device=dev)
+    if NS > 0:
+        U = miss_rows[0]           # rows that crossed the link in the last batch
+    nbytes = max(U, 1) * F * 2
+    flat = E_host.view(-1)[: max(U, 1) * F]
+    dst = torch.empty(max(U, 1) * F, dtype=torch.bfloat16, device=dev)
     link_med, _, _ = _median_ms(lambda: dst.copy_(flat, non_blocking=True), 5, 2)
     L.stem_profile_enable(ctx, True)
     L.stem_profile_reset(ctx)
@@ -356,8 +380,9 @@ def bench_host_table(args, shape, dev):
         "metric": "STEM FFN forward tokens/s, host-resident table", "value": round(T / (med * 1e-3), 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(med, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "n_uniq": U,
+        "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "n_uniq": uniq_rows[0],
                    "ids": "Zipf(s=1.1)" if args.ids == "zipf" else "uniform",
+                   "cache_slots": NS, "rows_over_the_link": U,
                    "step": "dedup + row copy over the host link (side stream) + forward"},
         "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4),
                        "device_resident_forward": round(res_med, 4), "exposed_by_host_table": round(med - res_med, 4),

@@ -185,6 +185,33 @@ stem_status stem_prefetch_rows(stem_ctx* ctx, const void* E_host, const int32_t*
                                void* E_compact, int64_t cap, int32_t* remap, int64_t* n_uniq_host,
                                int32_t* uniq_ids_host, void** ready_event);
 
+/* Host-resident table with a cache of the most frequently used rows on the device (System
+ * Implementation: LFU cache of hot rows, only misses are prefetched).
+ *
+ * stem_cache_init gives the context an empty cache of n_slots rows (0 removes it) and zero
+ * frequency counts; the bookkeeping is on the host, the rows live in the caller's buffer
+ * E_dev [n_slots + cap, F]: rows [0, n_slots) are cache slots, the rest is the staging area
+ * of one batch.  E_dev must stay the same buffer from call to call, and a batch's forward
+ * must have finished before the next stem_prefetch_rows_cached call overwrites the staging.
+ *
+ * stem_prefetch_rows_cached: counts every token of ids_host, maps each distinct id to its
+ * cache slot (hit) or to staging row n_slots + k, k numbering the misses in order of first
+ * use, copies the missed rows from E_host there on the side stream, writes remap (device
+ * [T]) so that stem_ffn_forward(E = E_dev, ids = remap, E_rows = n_slots + cap,
+ * wait_event = *ready_event) is the same layer, and then updates the cache for later
+ * batches: the missed rows are offered in order (frequency descending, id ascending); each
+ * takes a free slot (lowest first) or replaces the least frequent cached row this batch
+ * did not use (frequency ascending, id ascending) if it is strictly more frequent; the
+ * first candidate that fails ends the update; promoted rows are copied from their staging
+ * rows on the device.  *n_uniq_host, *n_miss_host (host) are valid on return.
+ * STEM_ERR_WORKSPACE if more than cap rows miss; STEM_ERR_ID_RANGE for an id outside [0, V).
+ * stem_cache_state copies the table row held by each slot (-1 = free) to host memory. */
+stem_status stem_cache_init(stem_ctx* ctx, int64_t n_slots);
+stem_status stem_prefetch_rows_cached(stem_ctx* ctx, const void* E_host, const int32_t* ids_host, int64_t T,
+                                      void* E_dev, int64_t cap, int32_t* remap, int64_t* n_uniq_host,
+                                      int64_t* n_miss_host, void** ready_event);
+stem_status stem_cache_state(stem_ctx* ctx, int32_t* id_in_slot_host, int64_t n_slots);
+
 /* ---- measurement aid ------------------------------------------------------------ */
 
 /* With profiling on, every kernel launch of the context is bracketed by HIP events on

@@ -84,6 +84,9 @@ void release(stem_ctx* c) {
   if (c->remap_pinned) (void)hipHostFree(c->remap_pinned);
   if (c->pack_pinned) (void)hipHostFree(c->pack_pinned);
   free(c->slot);
+  free(c->cache_id_in_slot); free(c->cache_slot_of); free(c->cache_freq);
+  if (c->inst_pinned) (void)hipHostFree(c->inst_pinned);
+  (void)hipFree(c->inst_dev);
   if (c->side) (void)hipStreamDestroy(c->side);
   if (c->ready) (void)hipEventDestroy(c->ready);
   for (int i = 0; i < 2; ++i) if (c->pack_done[i]) (void)hipEventDestroy(c->pack_done[i]);
@@ -664,6 +667,182 @@ stem_status stem_prefetch_rows(stem_ctx* c, const void* E_host, const int32_t* i
   }
   HIP_TRY(c, hipEventRecord(c->ready, c->side));
   *ready_event = c->ready;
+  return STEM_OK;
+}
+
+// ---- host-resident table with a device-resident cache of the most frequently used rows ----------
+
+stem_status stem_cache_init(stem_ctx* c, int64_t n_slots) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  if (n_slots < 0 || n_slots > INT32_MAX / 2)
+    return fail(c, STEM_ERR_SHAPE, "stem_cache_init: n_slots = %lld", (long long)n_slots);
+  const int V = c->desc.vocab;
+  HIP_TRY(c, hipSetDevice(c->device));
+  HIP_TRY(c, hipStreamSynchronize(c->side));
+  free(c->cache_id_in_slot); free(c->cache_slot_of); free(c->cache_freq);
+  c->cache_id_in_slot = nullptr; c->cache_slot_of = nullptr; c->cache_freq = nullptr;
+  c->cache_slots = 0;
+  if (n_slots == 0) return STEM_OK;
+  if (!c->inst_pinned) {   // lists of promoted rows: staging row, cache slot
+    HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->inst_pinned), std::max<size_t>(c->max_tokens, 1) * 8,
+                             hipHostMallocDefault));
+    HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&c->inst_dev), std::max<size_t>(c->max_tokens, 1) * 8));
+  }
+  c->cache_id_in_slot = static_cast<int32_t*>(malloc((size_t)n_slots * 4));
+  c->cache_slot_of = static_cast<int32_t*>(malloc((size_t)V * 4));
+  c->cache_freq = static_cast<uint32_t*>(calloc((size_t)V, 4));
+  if (!c->cache_id_in_slot || !c->cache_slot_of || !c->cache_freq)
+    return fail(c, STEM_ERR_HIP, "stem_cache_init: out of host memory");
+  memset(c->cache_id_in_slot, 0xff, (size_t)n_slots * 4);
+  memset(c->cache_slot_of, 0xff, (size_t)V * 4);
+  c->cache_slots = n_slots;
+  return STEM_OK;
+}
+
+stem_status stem_cache_state(stem_ctx* c, int32_t* id_in_slot_host, int64_t n) {
+  if (!c || !id_in_slot_host) return STEM_ERR_INVALID_ARG;
+  if (n != c->cache_slots) return fail(c, STEM_ERR_SHAPE, "stem_cache_state: n = %lld, cache has %lld slots",
+                                       (long long)n, (long long)c->cache_slots);
+  memcpy(id_in_slot_host, c->cache_id_in_slot, (size_t)n * 4);
+  return STEM_OK;
+}
+
+stem_status stem_prefetch_rows_cached(stem_ctx* c, const void* E_host, const int32_t* ids_host, int64_t T,
+                                      void* E_dev, int64_t cap, int32_t* remap, int64_t* n_uniq_host,
+                                      int64_t* n_miss_host, void** ready_event) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (c->cache_slots <= 0) return fail(c, STEM_ERR_INVALID_ARG, "stem_prefetch_rows_cached: call stem_cache_init first");
+  if (!E_host || (!ids_host && T > 0) || !E_dev || (!remap && T > 0) || !n_uniq_host || !n_miss_host || !ready_event)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_prefetch_rows_cached: null pointer argument");
+  if (misaligned(E_host) || misaligned(E_dev))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_prefetch_rows_cached: tables must be 16-byte aligned");
+  if (cap < 0) return fail(c, STEM_ERR_SHAPE, "stem_prefetch_rows_cached: cap = %lld", (long long)cap);
+  const int V = c->desc.vocab;
+  const int64_t NS = c->cache_slots;
+  const size_t row_bytes = (size_t)c->desc.d_ff * esize(c);
+  HIP_TRY(c, hipStreamSynchronize(c->side));   // pinned staging arrays are reused
+
+  for (int64_t i = 0; i < T; ++i)
+    if ((uint32_t)ids_host[i] >= (uint32_t)V)
+      return fail(c, STEM_ERR_ID_RANGE, "stem_prefetch_rows_cached: ids[%lld] = %d is outside [0, %d)", (long long)i,
+                  ids_host[i], V);
+
+  // One pass over the tokens.  c->slot marks the ids of this batch (-1 = not seen yet) and holds the
+  // row each one reads: its cache slot, or a staging row behind the cache, numbered in order of
+  // first use so that the rows the first tokens need cross the link first.
+  const int64_t tile_cols = (c->desc.d_model + 255) / 256;
+  int64_t chunk_tokens = std::max<int64_t>(1, STEM_PF_CHUNK_TILES / tile_cols) * 256;
+  chunk_tokens *= std::max<int64_t>(1, ((T + chunk_tokens - 1) / chunk_tokens + STEM_PF_MAX_CHUNKS - 1) / STEM_PF_MAX_CHUNKS);
+  int nchunks = (int)((T + chunk_tokens - 1) / chunk_tokens);
+  if (nchunks < 2) { nchunks = 1; chunk_tokens = std::max<int64_t>(T, 1); }
+  int64_t chunk_end[STEM_PF_MAX_CHUNKS] = {0};
+  int32_t* src_row = c->order_pinned;
+  int32_t* dst_row = c->order_pinned + c->max_tokens;
+  int64_t U = 0, n_miss = 0;
+  for (int64_t i = 0; i < T; ++i) {
+    const int32_t t = ids_host[i];
+    c->cache_freq[t] += 1;
+    int32_t v = c->slot[t];
+    if (v < 0) {   // first use in this batch
+      c->uniq_pinned[U++] = t;
+      v = c->cache_slot_of[t];
+      if (v < 0) {
+        v = (int32_t)(NS + n_miss);
+        if (n_miss < c->max_tokens) { src_row[n_miss] = t; dst_row[n_miss] = v; }
+        ++n_miss;
+      }
+      c->slot[t] = v;
+    }
+    c->remap_pinned[i] = v;
+    if ((i + 1) % chunk_tokens == 0 || i + 1 == T) chunk_end[std::min<int64_t>(i / chunk_tokens, nchunks - 1)] = n_miss;
+  }
+  *n_uniq_host = U;
+  *n_miss_host = n_miss;
+  c->pf_chunks = 0;
+  if (n_miss > cap) {
+    for (int64_t j = 0; j < U; ++j) c->slot[c->uniq_pinned[j]] = -1;
+    return fail(c, STEM_ERR_WORKSPACE, "stem_prefetch_rows_cached: %lld rows missed the cache but the staging area holds %lld",
+                (long long)n_miss, (long long)cap);
+  }
+
+  if (T > 0) HIP_TRY(c, hipMemcpyAsync(remap, c->remap_pinned, (size_t)T * 4, hipMemcpyHostToDevice, c->side));
+  if (n_miss > 0) {
+    HIP_TRY(c, hipMemcpyAsync(c->order_dev, src_row, (size_t)n_miss * 4, hipMemcpyHostToDevice, c->side));
+    HIP_TRY(c, hipMemcpyAsync(c->order_dev + c->max_tokens, dst_row, (size_t)n_miss * 4, hipMemcpyHostToDevice, c->side));
+  }
+  {
+    int64_t k0 = 0;
+    for (int k = 0; k < nchunks; ++k) {
+      HIP_TRY(c, stem_copy_rows_kernel(c, E_host, c->order_dev + k0, c->order_dev + c->max_tokens + k0,
+                                       chunk_end[k] - k0, (int64_t)row_bytes, E_dev, c->side));
+      k0 = chunk_end[k];
+      if (nchunks > 1) HIP_TRY(c, hipEventRecord(c->pf_ev[k], c->side));
+    }
+    if (nchunks > 1) { c->pf_chunks = nchunks; c->pf_T = T; c->pf_chunk_tokens = chunk_tokens; }
+  }
+  HIP_TRY(c, hipEventRecord(c->ready, c->side));
+  *ready_event = c->ready;
+
+  // Cache update for the batches to come (least frequently used): the rows missed now are offered
+  // in order (frequency descending, id ascending); each takes a free slot (lowest first) or replaces
+  // the coldest cached row this batch did not use (frequency ascending, id ascending) if it is
+  // strictly more frequent; the first candidate that fails ends the update.  A promoted row is
+  // copied device-to-device from its staging row, behind this batch's copies on the side stream.
+  struct Ent { uint32_t f; int32_t id; int32_t aux; };
+  std::vector<int32_t> free_slots;
+  std::vector<Ent> cold, cand;
+  uint32_t fmax = 0;
+  for (int64_t k = 0; k < n_miss; ++k) fmax = std::max(fmax, c->cache_freq[src_row[k]]);
+  uint32_t cold_min = UINT32_MAX;
+  for (int64_t sidx = 0; sidx < NS; ++sidx) {
+    const int32_t t = c->cache_id_in_slot[sidx];
+    if (t < 0) { free_slots.push_back((int32_t)sidx); continue; }
+    if (c->slot[t] >= 0) continue;                 // used by this batch: stays
+    const uint32_t f = c->cache_freq[t];
+    cold_min = std::min(cold_min, f);
+    if (f < fmax) cold.push_back({f, t, (int32_t)sidx});   // only these can lose to a candidate
+  }
+  for (int64_t k = 0; k < n_miss; ++k) {
+    const uint32_t f = c->cache_freq[src_row[k]];
+    if (!free_slots.empty() || f > cold_min) cand.push_back({f, src_row[k], (int32_t)k});
+  }
+  std::sort(cand.begin(), cand.end(), [](const Ent& a, const Ent& b) { return a.f != b.f ? a.f > b.f : a.id < b.id; });
+  {  // only the coldest |cand| rows can be replaced: select them, then order them
+    auto colder = [](const Ent& a, const Ent& b) { return a.f != b.f ? a.f < b.f : a.id < b.id; };
+    if (cold.size() > cand.size()) {
+      std::nth_element(cold.begin(), cold.begin() + cand.size(), cold.end(), colder);
+      cold.resize(cand.size());
+    }
+    std::sort(cold.begin(), cold.end(), colder);
+  }
+  int64_t n_inst = 0;
+  size_t nf = 0, nc = 0;
+  for (const Ent& e : cand) {
+    int32_t sidx;
+    if (nf < free_slots.size()) {
+      sidx = free_slots[nf++];
+    } else if (nc < cold.size() && e.f > cold[nc].f) {
+      sidx = cold[nc].aux;
+      c->cache_slot_of[cold[nc].id] = -1;
+      ++nc;
+    } else {
+      break;
+    }
+    c->cache_id_in_slot[sidx] = e.id;
+    c->cache_slot_of[e.id] = sidx;
+    c->inst_pinned[n_inst] = (int32_t)(NS + e.aux);        // staging row that holds it
+    c->inst_pinned[c->max_tokens + n_inst] = sidx;         // cache slot it moves to
+    ++n_inst;
+  }
+  for (int64_t j = 0; j < U; ++j) c->slot[c->uniq_pinned[j]] = -1;
+  if (n_inst > 0) {
+    HIP_TRY(c, hipMemcpyAsync(c->inst_dev, c->inst_pinned, (size_t)n_inst * 4, hipMemcpyHostToDevice, c->side));
+    HIP_TRY(c, hipMemcpyAsync(c->inst_dev + c->max_tokens, c->inst_pinned + c->max_tokens, (size_t)n_inst * 4,
+                              hipMemcpyHostToDevice, c->side));
+    HIP_TRY(c, stem_copy_rows_kernel(c, E_dev, c->inst_dev, c->inst_dev + c->max_tokens, n_inst, (int64_t)row_bytes,
+                                     E_dev, c->side));
+  }
   return STEM_OK;
 }
 

@@ -79,6 +79,15 @@ struct stem_ctx {
   size_t pack_bytes;
   hipEvent_t pack_done[2];
 
+  // device-resident cache of hot rows in host-resident mode (host-side bookkeeping; the rows
+  // themselves live in the caller's buffer)
+  int64_t cache_slots;       // 0 = no cache
+  int32_t* cache_id_in_slot; // host [cache_slots], -1 = free
+  int32_t* cache_slot_of;    // host [V], -1 = not cached
+  uint32_t* cache_freq;      // host [V]: token occurrences seen so far
+  int32_t* inst_pinned;      // pinned host [2 * max_tokens]: promoted rows (staging row, then cache slot)
+  int32_t* inst_dev;         // device [2 * max_tokens]
+
   // profiling
   int prof_on;
   hipEvent_t* prof_ev;   // 2 * STEM_MAX_PROF_EVENTS

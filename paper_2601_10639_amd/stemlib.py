@@ -23,7 +23,8 @@ SYMBOLS = [
     "stem_create", "stem_destroy", "stem_last_error", "stem_status_string", "stem_sync_status",
     "stem_ffn_forward", "stem_ffn_backward", "stem_ffn_up_forward", "stem_ffn_up_backward",
     "stem_embed_grad", "stem_embed_sparse_adamw",
-    "stem_prefetch_rows", "stem_profile_enable", "stem_profile_kernels", "stem_profile_read",
+    "stem_prefetch_rows", "stem_cache_init", "stem_prefetch_rows_cached", "stem_cache_state",
+    "stem_profile_enable", "stem_profile_kernels", "stem_profile_read",
     "stem_profile_reset",
 ]
 
@@ -82,6 +83,13 @@ def lib() -> ctypes.CDLL:
         L.stem_prefetch_rows.argtypes = [vp, vp, vp, i64, vp, i64, vp, ctypes.POINTER(i64), vp,
                                          ctypes.POINTER(vp)]
         L.stem_prefetch_rows.restype = i32
+        L.stem_cache_init.argtypes = [vp, i64]
+        L.stem_cache_init.restype = i32
+        L.stem_prefetch_rows_cached.argtypes = [vp, vp, vp, i64, vp, i64, vp, ctypes.POINTER(i64),
+                                                ctypes.POINTER(i64), ctypes.POINTER(vp)]
+        L.stem_prefetch_rows_cached.restype = i32
+        L.stem_cache_state.argtypes = [vp, vp, i64]
+        L.stem_cache_state.restype = i32
         L.stem_profile_enable.argtypes = [vp, i32]
         L.stem_profile_enable.restype = i32
         L.stem_profile_kernels.argtypes = []
@@ -264,6 +272,35 @@ def stem_prefetch_rows(ctx: StemCtx, E_host, ids_host, E_compact, remap, uniq_id
                                   ctypes.byref(ev))
     _check(ctx, st, "stem_prefetch_rows")
     return n.value, ev.value
+
+
+def stem_cache_init(ctx: StemCtx, n_slots: int):
+    _check(ctx, lib().stem_cache_init(ctx.handle, n_slots), "stem_cache_init")
+
+
+def stem_prefetch_rows_cached(ctx: StemCtx, E_host, ids_host, E_dev, n_slots: int, remap, T=None):
+    """E_dev holds n_slots cache rows followed by the staging area.  Returns (n_uniq, n_miss, ready_event)."""
+    if not E_host.is_pinned():
+        raise ValueError("E_host must be pinned host memory")
+    T = ids_host.shape[0] if T is None else T
+    n = ctypes.c_int64(0)
+    nm = ctypes.c_int64(0)
+    ev = ctypes.c_void_p(None)
+    st = lib().stem_prefetch_rows_cached(ctx.handle, _ptr(E_host, ctx.torch_dtype, cuda=False, name="E_host"),
+                                         _ptr(ids_host, torch.int32, cuda=False, name="ids_host"), T,
+                                         _ptr(E_dev, ctx.torch_dtype, name="E_dev"), E_dev.shape[0] - n_slots,
+                                         _ptr(remap, torch.int32, name="remap"), ctypes.byref(n), ctypes.byref(nm),
+                                         ctypes.byref(ev))
+    _check(ctx, st, "stem_prefetch_rows_cached")
+    return n.value, nm.value, ev.value
+
+
+def stem_cache_state(ctx: StemCtx, n_slots: int):
+    """Table row held by each cache slot (-1 = free), as a CPU int32 tensor."""
+    out = torch.empty(n_slots, dtype=torch.int32)
+    _check(ctx, lib().stem_cache_state(ctx.handle, _ptr(out, torch.int32, cuda=False, name="out"), n_slots),
+           "stem_cache_state")
+    return out
 
 
 def stem_profile_enable(ctx: StemCtx, on: bool):

@@ -193,6 +193,50 @@ def test_prefetch_rows_chunked_with_ragged_last_chunk():
     assert Hn.max_rel(y.float().cpu(), ref) <= Hn.TOL["bf16"]
 
 
+@pytest.mark.parametrize("T,d", [(3000, 128), (20000, 2048)])   # 20000 tokens at d_model 2048: three chunks
+def test_lfu_row_cache_stream_matches_the_oracle_policy(T, d):
+    """Ten batches of one Zipf stream through the cached prefetch: remap, miss count and the content
+    of every cache slot equal the oracle's policy bit for bit; every token finds its own row in the
+    device buffer; the layer computed from it matches the oracle."""
+    V, F, n_slots = 5000, 128, 600
+    shape = inputs.StemShape("host-cached", d, F, V, 1, T, "bf16")
+    ctx = Hn.make_ctx(shape, T)
+    E_host = inputs.normal((V, F), 0.02, 61, torch.bfloat16, "cpu").pin_memory()
+    E_dev = torch.zeros(n_slots + T, F, dtype=torch.bfloat16, device=DEV)
+    remap = torch.empty(T, dtype=torch.int32, device=DEV)
+    x = inputs.normal((T, d), 1.0, 62, torch.bfloat16, DEV)
+    Wg = inputs.normal((F, d), 0.02, 63, torch.bfloat16, DEV)
+    Wd = inputs.normal((d, F), 0.02, 64, torch.bfloat16, DEV)
+    y = torch.empty(T, d, dtype=torch.bfloat16, device=DEV)
+    L.stem_cache_init(ctx, n_slots)
+    ref_cache = O.LfuRowCache(V, n_slots)
+    hits = []
+    for b in range(10):
+        ids_np = inputs.zipf_ids(T, V, seed=200 + b, perm_seed=9)
+        o_remap, o_misses, _ = ref_cache.step(ids_np)
+        n_uniq, n_miss, ev = L.stem_prefetch_rows_cached(ctx, E_host, torch.from_numpy(ids_np), E_dev, n_slots, remap)
+        L.stem_ffn_forward(ctx, x, remap, Wg, Wd, E_dev, y, wait_event=ev)
+        torch.cuda.synchronize()
+        L.stem_sync_status(ctx)
+        assert n_uniq == len(np.unique(ids_np)) and n_miss == len(o_misses)
+        np.testing.assert_array_equal(remap.cpu().numpy(), o_remap)
+        np.testing.assert_array_equal(L.stem_cache_state(ctx, n_slots).numpy(), np.asarray(ref_cache.id_in_slot))
+        rows = E_dev[remap.long()].cpu().view(torch.int16)
+        assert torch.equal(rows, E_host[torch.from_numpy(ids_np.astype(np.int64))].view(torch.int16))
+        state = L.stem_cache_state(ctx, n_slots).long()
+        used = state >= 0
+        assert torch.equal(E_dev[:n_slots][used.to(DEV)].cpu().view(torch.int16), E_host[state[used]].view(torch.int16))
+        hits.append(1.0 - n_miss / n_uniq)
+    tok = np.arange(0, T, max(1, T // 64))
+    uniq_t, remap_t = np.unique(ids_np[tok], return_inverse=True)
+    ref, _ = O.ffn_forward(_rows(x, tok), remap_t, inputs.to_f64(Wg), inputs.to_f64(Wd),
+                           inputs.to_f64(E_host[torch.from_numpy(uniq_t.astype(np.int64))]))
+    assert Hn.max_rel(_rows(y, tok), ref) <= Hn.TOL["bf16"]
+    assert hits[0] == 0.0 and hits[-1] > 0.15, hits   # rows (not tokens) served from the cache
+    print("row hit rate per batch", [round(h, 2) for h in hits])
+    ctx.close()
+
+
 def test_prefetch_rows_errors():
     shape = inputs.StemShape("host-err", 64, 64, 100, 1, 50, "bf16")
     ctx = Hn.make_ctx(shape, 50)
