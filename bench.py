@@ -38,6 +38,9 @@ def main() -> int:
     ap.add_argument("--ids", default="zipf", choices=["zipf", "uniform"], help="id distribution for C5")
     ap.add_argument("--cache-slots", type=int, default=0,
                     help="C5: device-resident LFU cache of this many rows (0 = none); ten batches warm it first")
+    ap.add_argument("--host-state", action="store_true",
+                    help="C2/C3: training step with the table, its fp32 master and the AdamW moments in pinned host "
+                         "memory (rows prefetched, optimiser straight on the host-resident state)")
     ap.add_argument("--variant", default="stem", choices=["stem", "dense", "additive"],
                     help="stem: the STEM layer (the headline); dense: SwiGLU FFN with an up projection and no table; "
                          "additive: up projection plus table (C2, C3 only)")
@@ -66,6 +69,8 @@ def main() -> int:
         return bench_decode(args, shape, dev)
     if args.workload == "C5":
         return bench_host_table(args, shape, dev)
+    if args.host_state:
+        return bench_host_training(args, shape, dev)
     T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
     bf16 = shape.dtype == "bf16"
     dt = inputs.torch_dtype(shape.dtype)
@@ -391,6 +396,83 @@ def bench_host_table(args, shape, dev):
                      round(nbytes / (copy_ms * 1e-3) / 1e9, 2), "peak": round(nbytes / (link_med * 1e-3) / 1e9, 2),
                      "unit": "GB/s", "frac": None if not copy_ms else round(link_med / copy_ms, 4), "traffic": None,
                      "bytes": nbytes, "peak_is": "measured contiguous pinned host-to-device copy of the same size"},
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
+def bench_host_training(args, shape, dev):
+    """One training step of the layer with the table and its optimiser state resident in pinned host
+    memory: de-duplicate, prefetch the distinct rows, forward and backward on the compact rows, table
+    gradient, sparse AdamW reading and writing the touched rows of master / m / v / table over the link."""
+    import torch
+
+    from paper_2601_10639_amd import inputs, stemlib as L
+
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    bf = torch.bfloat16
+    inp = inputs.layer_inputs(shape, seed=3, device=dev)
+    ids_host = inp["ids"].cpu()
+    E_host = inp["E"].cpu().pin_memory()
+    master = E_host.float().pin_memory()
+    m = torch.zeros(V, F).pin_memory()
+    v = torch.zeros(V, F).pin_memory()
+    del inp["E"]
+    ctx = L.stem_create(d, F, V, L.STEM_BF16, T, 0)
+    y, dx = (torch.empty(T, d, dtype=bf, device=dev) for _ in range(2))
+    G, H, dU = (torch.empty(T, F, dtype=bf, device=dev) for _ in range(3))
+    dWg = torch.empty(F, d, dtype=torch.float32, device=dev)
+    dWd = torch.empty(d, F, dtype=torch.float32, device=dev)
+    E_compact = torch.empty(T, F, dtype=bf, device=dev)
+    remap = torch.empty(T, dtype=torch.int32, device=dev)
+    uniq_host = torch.empty(T, dtype=torch.int32).pin_memory()
+    uniq_dev = torch.empty(T, dtype=torch.int32, device=dev)
+    i32 = torch.int32
+    sorted_ids, perm = (torch.empty(T, dtype=i32, device=dev) for _ in range(2))
+    uq = torch.empty(T, dtype=i32, device=dev)
+    seg_offsets = torch.empty(T + 1, dtype=i32, device=dev)
+    n_uniq = torch.zeros(1, dtype=i32, device=dev)
+    dE_rows = torch.empty(T, F, dtype=torch.float32, device=dev)
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    step_no, U = [0], [0]
+
+    def step():
+        step_no[0] += 1
+        n, ev = L.stem_prefetch_rows(ctx, E_host, ids_host, E_compact, remap, uniq_host)
+        U[0] = n
+        uniq_dev[:n].copy_(uniq_host[:n], non_blocking=True)
+        L.stem_ffn_forward(ctx, inp["x"], remap, inp["W_gate"], inp["W_down"], E_compact, y, G, H, wait_event=ev,
+                           E_rows=n)
+        L.stem_ffn_backward(ctx, inp["dy"], inp["x"], remap, inp["W_gate"], inp["W_down"], E_compact, G, H, dx, dWg,
+                            dWd, dU, E_rows=n)
+        L.stem_embed_grad(ctx, remap, dU, sorted_ids, perm, uq, seg_offsets, n_uniq, dE_rows)
+        L.stem_embed_sparse_adamw(ctx, uniq_dev, n_uniq, dE_rows, E_host, master, m, v, step=step_no[0], **hp)
+
+    med, p10, p90 = _median_ms(step, args.steps, args.warmup)
+    L.stem_sync_status(ctx)
+    L.stem_profile_enable(ctx, True)
+    L.stem_profile_reset(ctx)
+    for _ in range(3):
+        step()
+    prof = L.stem_profile_read(ctx)
+    L.stem_profile_enable(ctx, False)
+    kernels = {k: {"avg_ms": round(val[0] / val[1], 5), "launches": val[1]} for k, val in prof.items()}
+    n = U[0]
+    ad = kernels["sparse_adamw"]["avg_ms"]
+    rd, wr = n * F * 12, n * F * 14          # master, m, v read; master, m, v, bf16 row written
+    out = {
+        "metric": "STEM FFN fwd+bwd tokens/s per layer, table and optimiser state in host memory",
+        "value": round(T / (med * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(med, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "n_uniq": n,
+                   "ids": "Zipf(s=1.1)", "step": "dedup+prefetch+fwd+bwd+embed_grad+sparse_adamw on host-resident state"},
+        "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4)},
+        "roofline": {"bound": "host link", "kernel": "sparse_adamw", "achieved": round(max(rd, wr) / (ad * 1e-3) / 1e9, 2),
+                     "peak": None, "unit": "GB/s in the busier direction", "frac": None, "traffic": None,
+                     "bytes": {"read_over_link": rd, "written_over_link": wr}},
         "kernels": kernels,
     }
     print(json.dumps(out))

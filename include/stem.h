@@ -138,7 +138,12 @@ stem_status stem_embed_grad(stem_ctx* ctx, const int32_t* ids, const void* dU, i
  * p is master[r] (fp32).  For STEM_BF16, E[r] receives p rounded to nearest-even
  * bfloat16; for STEM_F32 `master` may be NULL and E itself is p.  m, v [V,F] fp32.
  * Rows not listed are not read or written.  uniq_ids, n_uniq: device, as produced by
- * stem_embed_grad; max_rows = capacity of uniq_ids / dE_rows (rows).  hp: host. */
+ * stem_embed_grad; max_rows = capacity of uniq_ids / dE_rows (rows).  hp: host.
+ * E, master, m, v may also live in pinned host memory (hipHostMalloc; training with a
+ * host-resident table, System Implementation): the kernel then reads the touched rows of
+ * master, m, v over the host link and writes them and the bf16 row back in the same pass,
+ * so nothing but the touched rows ever moves.  Rows of E that a device-side copy or cache
+ * holds (E_compact, the LFU cache) are not refreshed by this call. */
 stem_status stem_embed_sparse_adamw(stem_ctx* ctx, const int32_t* uniq_ids, const int32_t* n_uniq,
                                     int64_t max_rows, const float* dE_rows, void* E, float* master,
                                     float* m, float* v, const stem_adamw_hparams* hp, void* stream);

@@ -150,6 +150,10 @@ def _ptr(t, dtype=None, cuda=True, name="tensor") -> ctypes.c_void_p:
         raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
     if not t.is_contiguous():
         raise ValueError(f"{name}: must be contiguous")
+    if cuda == "or_pinned":
+        if not (t.is_cuda or t.is_pinned()):
+            raise ValueError(f"{name}: must be device memory or pinned host memory")
+        return ctypes.c_void_p(t.data_ptr())
     if cuda and not t.is_cuda:
         raise ValueError(f"{name}: must be device memory")
     if not cuda and t.is_cuda:
@@ -246,14 +250,17 @@ def stem_embed_grad(ctx: StemCtx, ids, dU, sorted_ids, perm, uniq_ids, seg_offse
 
 def stem_embed_sparse_adamw(ctx: StemCtx, uniq_ids, n_uniq, dE_rows, E, master, m, v, lr, beta1, beta2, eps,
                             weight_decay, step, stream=None, max_rows=None):
+    """E, master, m, v may be pinned host tensors (table and optimiser state resident in host memory)."""
     hp = stem_adamw_hparams(lr, beta1, beta2, eps, weight_decay, step)
     f32 = torch.float32
     max_rows = dE_rows.shape[0] if max_rows is None else max_rows
     st = lib().stem_embed_sparse_adamw(ctx.handle, _ptr(uniq_ids, torch.int32, name="uniq_ids"),
                                        _ptr(n_uniq, torch.int32, name="n_uniq"), max_rows,
-                                       _ptr(dE_rows, f32, name="dE_rows"), _ptr(E, ctx.torch_dtype, name="E"),
-                                       _ptr(master, f32, name="master"), _ptr(m, f32, name="m"),
-                                       _ptr(v, f32, name="v"), ctypes.byref(hp), _stream(stream))
+                                       _ptr(dE_rows, f32, name="dE_rows"),
+                                       _ptr(E, ctx.torch_dtype, cuda="or_pinned", name="E"),
+                                       _ptr(master, f32, cuda="or_pinned", name="master"),
+                                       _ptr(m, f32, cuda="or_pinned", name="m"),
+                                       _ptr(v, f32, cuda="or_pinned", name="v"), ctypes.byref(hp), _stream(stream))
     _check(ctx, st, "stem_embed_sparse_adamw")
 
 

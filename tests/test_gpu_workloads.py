@@ -237,6 +237,69 @@ def test_lfu_row_cache_stream_matches_the_oracle_policy(T, d):
     ctx.close()
 
 
+def test_training_steps_with_host_resident_table_and_optimiser_state():
+    """Three training steps with the table, its fp32 master and the AdamW moments in pinned host
+    memory: rows prefetched, forward and backward on the compact rows, table gradient, sparse AdamW
+    straight on the host-resident state.  The oracle runs the same three steps on its own arrays."""
+    T, d, F, V = 1500, 128, 256, 3000
+    shape = inputs.StemShape("host-train", d, F, V, 1, T, "bf16")
+    bf = torch.bfloat16
+    ctx = Hn.make_ctx(shape, T)
+    E_host = inputs.normal((V, F), 0.02, 71, bf, "cpu").pin_memory()
+    master = E_host.float().pin_memory()
+    m = torch.zeros(V, F).pin_memory()
+    v = torch.zeros(V, F).pin_memory()
+    Wg = inputs.normal((F, d), 0.02, 72, bf, DEV)
+    Wd = inputs.normal((d, F), 0.02, 73, bf, DEV)
+    o_master, o_m, o_v = inputs.to_f64(E_host), np.zeros((V, F)), np.zeros((V, F))
+    o_E = o_master.copy()
+    E0 = E_host.float().numpy().copy()
+    touched = np.zeros(0, dtype=np.int64)
+    E_compact = torch.empty(T, F, dtype=bf, device=DEV)
+    remap = torch.empty(T, dtype=torch.int32, device=DEV)
+    uniq_host = torch.empty(T, dtype=torch.int32)
+    y, dx = (torch.empty(T, d, dtype=bf, device=DEV) for _ in range(2))
+    G, H, dU = (torch.empty(T, F, dtype=bf, device=DEV) for _ in range(3))
+    dWg = torch.empty(F, d, dtype=torch.float32, device=DEV)
+    dWd = torch.empty(d, F, dtype=torch.float32, device=DEV)
+    for step in range(1, 4):
+        ids_np = inputs.zipf_ids(T, V, seed=80 + step, perm_seed=3)
+        x = inputs.normal((T, d), 1.0, 90 + step, bf, DEV)
+        dy = inputs.normal((T, d), 1.0, 95 + step, bf, DEV)
+        n, ev = L.stem_prefetch_rows(ctx, E_host, torch.from_numpy(ids_np), E_compact, remap, uniq_host)
+        L.stem_ffn_forward(ctx, x, remap, Wg, Wd, E_compact, y, G, H, wait_event=ev, E_rows=n)
+        L.stem_ffn_backward(ctx, dy, x, remap, Wg, Wd, E_compact, G, H, dx, dWg, dWd, dU, E_rows=n)
+        # the compact slots are the distinct ids in ascending order, so the gradient rows of the slots
+        # are the gradient rows of the table rows uniq_host[:n]
+        eg = Hn.hip_embed_grad(ctx, remap, dU, n)
+        assert int(eg["n_uniq"].item()) == n
+        L.stem_embed_sparse_adamw(ctx, uniq_host[:n].to(DEV), eg["n_uniq"], eg["dE_rows"], E_host, master, m, v,
+                                  step=step, **Hn.ADAMW)
+        torch.cuda.synchronize()
+        L.stem_sync_status(ctx)
+        # oracle: same step on the bf16 table it holds, its own gradients, its own state
+        bw = O.ffn_backward(inputs.to_f64(dy), inputs.to_f64(x), ids_np, inputs.to_f64(Wg), inputs.to_f64(Wd), o_E)
+        oeg = O.embed_grad(ids_np, bw["dU"])
+        np.testing.assert_array_equal(uniq_host[:n].numpy(), oeg["uniq_ids"])
+        assert Hn.max_rel(eg["dE_rows"][:n].cpu(), oeg["dE_rows"]) <= Hn.TOL["bf16"]
+        o_master, o_m, o_v = O.sparse_adamw(oeg["uniq_ids"], oeg["dE_rows"], o_master, o_m, o_v, step=step, **Hn.ADAMW)
+        o_E = O.bf16_round(o_master)
+        assert Hn.max_rel(m.numpy(), o_m) <= Hn.TOL["bf16"]
+        assert Hn.max_rel(v.numpy(), o_v) <= 2 * Hn.TOL["bf16"]
+        # rows no batch has named so far: bit-identical to the initial table on both sides; the bf16
+        # table is the rounded master everywhere
+        touched = np.union1d(touched, oeg["uniq_ids"])
+        untouched = np.setdiff1d(np.arange(V), touched)
+        np.testing.assert_array_equal(master.numpy()[untouched], E0[untouched])
+        np.testing.assert_array_equal(o_master[untouched].astype(np.float32), E0[untouched])
+        assert torch.equal(E_host.view(torch.int16), master.to(bf).view(torch.int16))
+        if step == 1:   # the first update is lr * sign(g): compare where the sign of g is beyond its error bound
+            sure = np.abs(oeg["dE_rows"]) > 2 * Hn.TOL["bf16"] * np.abs(oeg["dE_rows"]).max()
+            diff = np.abs(master.numpy()[oeg["uniq_ids"]] - o_master[oeg["uniq_ids"]])[sure].max()
+            assert sure.any() and diff / np.abs(o_master).max() <= 1e-5, diff
+    ctx.close()
+
+
 def test_prefetch_rows_errors():
     shape = inputs.StemShape("host-err", 64, 64, 100, 1, 50, "bf16")
     ctx = Hn.make_ctx(shape, 50)
