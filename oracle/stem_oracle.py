@@ -330,6 +330,63 @@ class LfuRowCache:
 
 
 # ----------------------------------------------------------------------------
+# knowledge editing: replacing the rows of a source entity's tokens by a target entity's
+# (Experiments / appendix, "knowledge editing" of STEM embeddings)
+# ----------------------------------------------------------------------------
+EDIT_REPLACE, EDIT_PAD_LEFT, EDIT_COPY, EDIT_AVERAGE = 0, 1, 2, 3
+
+
+def edit_target_index(n_s: int, n_t: int, mode: int):
+    """For each of the n_s source positions, the index of the target token whose row replaces
+    it; -1 = the padding token's row; None for EDIT_AVERAGE (every position gets the mean).
+
+    EDIT_REPLACE: equal lengths, one to one.  EDIT_PAD_LEFT (n_s >= n_t): the target sequence
+    padded on the left to n_s tokens.  EDIT_COPY (n_s >= n_t): every target token repeated
+    floor(n_s / n_t) times and the last one repeated further to cover all n_s positions.
+    """
+    if n_s < 1 or n_t < 1:
+        raise ValueError("both entities need at least one token")
+    if mode == EDIT_AVERAGE:
+        return None
+    if mode == EDIT_REPLACE:
+        if n_s != n_t:
+            raise ValueError("one-to-one replacement needs equal token counts")
+        return list(range(n_s))
+    if n_s < n_t:
+        raise ValueError("padding and copying need a source span at least as long as the target")
+    if mode == EDIT_PAD_LEFT:
+        return [-1] * (n_s - n_t) + list(range(n_t))
+    if mode == EDIT_COPY:
+        r = n_s // n_t
+        out = []
+        for k in range(n_t):
+            out += [k] * r
+        out += [n_t - 1] * (n_s - len(out))
+        return out
+    raise ValueError("unknown edit mode")
+
+
+def edit_rows(E, src_ids, tgt_ids, mode: int, pad_id: int = 0, round_row=None):
+    """Returns (edited copy of the table, the original rows of the source tokens).  All
+    replacement rows are taken from the table as it was before the edit.  The mean of
+    EDIT_AVERAGE is rounded by `round_row` (e.g. bf16_round) if given."""
+    E = np.asarray(E, dtype=np.float64)
+    src = [int(t) for t in src_ids]
+    tgt = [int(t) for t in tgt_ids]
+    idx = edit_target_index(len(src), len(tgt), mode)
+    if idx is None:
+        mean = E[tgt].sum(axis=0) / len(tgt)
+        rows = np.tile(mean if round_row is None else round_row(mean), (len(src), 1))
+    else:
+        rows = np.stack([E[pad_id] if k < 0 else E[tgt[k]] for k in idx])
+    out = E.copy()
+    backup = E[src].copy()
+    for j, t in enumerate(src):
+        out[t] = rows[j]
+    return out, backup
+
+
+# ----------------------------------------------------------------------------
 # stacked decode chain (several STEM layers joined by a residual stream)
 # ----------------------------------------------------------------------------
 def decode_chain(x0, ids, layers, round_stream=bf16_round):

@@ -411,6 +411,53 @@ def test_lfu_row_cache_serves_right_rows_and_keeps_the_most_frequent():
     assert 0.5 < hit_tokens / total < 0.75, hit_tokens / total
 
 
+def test_edit_target_index_follows_the_stated_rules():
+    # one to one; left padding; "each target token repeated floor(n_s / n_t) times, the last one
+    # repeated as needed to cover the n_s source positions"
+    assert O.edit_target_index(3, 3, O.EDIT_REPLACE) == [0, 1, 2]
+    assert O.edit_target_index(4, 2, O.EDIT_PAD_LEFT) == [-1, -1, 0, 1]
+    assert O.edit_target_index(4, 2, O.EDIT_COPY) == [0, 0, 1, 1]
+    assert O.edit_target_index(5, 2, O.EDIT_COPY) == [0, 0, 1, 1, 1]
+    assert O.edit_target_index(7, 3, O.EDIT_COPY) == [0, 0, 1, 1, 2, 2, 2]
+    assert O.edit_target_index(3, 3, O.EDIT_COPY) == [0, 1, 2] == O.edit_target_index(3, 3, O.EDIT_PAD_LEFT)
+    assert O.edit_target_index(4, 9, O.EDIT_AVERAGE) is None
+    for n_s, n_t in itertools.product(range(1, 9), repeat=2):
+        if n_s >= n_t:
+            idx = O.edit_target_index(n_s, n_t, O.EDIT_COPY)
+            counts = [idx.count(k) for k in range(n_t)]
+            assert len(idx) == n_s and idx == sorted(idx)
+            assert counts[:-1] == [n_s // n_t] * (n_t - 1) and counts[-1] == n_s - (n_s // n_t) * (n_t - 1)
+    for bad in ((2, 3, O.EDIT_REPLACE), (2, 3, O.EDIT_COPY), (2, 3, O.EDIT_PAD_LEFT), (0, 1, O.EDIT_COPY)):
+        with pytest.raises(ValueError):
+            O.edit_target_index(*bad)
+
+
+def test_edit_rows_equals_substituting_the_tokens():
+    # editing the table rows of the source tokens is the same layer as feeding the target tokens
+    # at the source positions (when the source tokens occur nowhere else); sources and targets may overlap
+    rng = np.random.default_rng(41)
+    V, F, d = 12, 5, 4
+    E, Wg, Wd = rng.normal(size=(V, F)), rng.normal(size=(F, d)), rng.normal(size=(d, F))
+    src, tgt, pad = [3, 7, 8, 1], [7, 5], 0
+    for mode in (O.EDIT_PAD_LEFT, O.EDIT_COPY):
+        edited, backup = O.edit_rows(E, src, tgt, mode, pad)
+        np.testing.assert_array_equal(backup, E[src])
+        idx = O.edit_target_index(len(src), len(tgt), mode)
+        ids = np.asarray([2] + src + [9])
+        sub = np.asarray([2] + [pad if k < 0 else tgt[k] for k in idx] + [9])
+        x = rng.normal(size=(len(ids), d))
+        np.testing.assert_array_equal(O.ffn_forward(x, ids, Wg, Wd, edited)[0], O.ffn_forward(x, sub, Wg, Wd, E)[0])
+        untouched = [t for t in range(V) if t not in src]
+        np.testing.assert_array_equal(edited[untouched], E[untouched])
+    swapped, _ = O.edit_rows(E, [3, 7], [7, 3], O.EDIT_REPLACE)          # a swap reads the old rows
+    np.testing.assert_array_equal(swapped[[3, 7]], E[[7, 3]])
+    avg, _ = O.edit_rows(E, src, [5, 6, 11], O.EDIT_AVERAGE)
+    np.testing.assert_allclose(avg[src], np.tile(np.mean(E[[5, 6, 11]], axis=0), (4, 1)), rtol=1e-15)
+    undone = avg.copy()
+    undone[src] = O.edit_rows(E, src, [5, 6, 11], O.EDIT_AVERAGE)[1]
+    np.testing.assert_array_equal(undone, E)
+
+
 def test_decode_chain_composes_layers_with_rounded_residual():
     rng = np.random.default_rng(21)
     T, d, F, V = 4, 8, 16, 5
