@@ -217,6 +217,28 @@ stem_status stem_prefetch_rows_cached(stem_ctx* ctx, const void* E_host, const i
                                       int64_t* n_miss_host, void** ready_event);
 stem_status stem_cache_state(stem_ctx* ctx, int32_t* id_in_slot_host, int64_t n_slots);
 
+/* ---- knowledge editing (the paper's editing of STEM embeddings: the rows of a source
+ *      entity's tokens are replaced by rows of a target entity's tokens) ------------ */
+
+typedef enum {
+  STEM_EDIT_REPLACE = 0,  /* n_s == n_t: source token j receives target token j's row */
+  STEM_EDIT_PAD_LEFT = 1, /* n_s >= n_t: the target sequence padded on the left with pad_id */
+  STEM_EDIT_COPY = 2,     /* n_s >= n_t: each target token floor(n_s/n_t) times, the last repeated to fill */
+  STEM_EDIT_AVERAGE = 3   /* any lengths: every source token receives the mean of the target rows */
+} stem_edit_mode;
+
+/* Overwrites rows E[src_ids[j]], j < n_s, of one layer's table (device, [V,F], context dtype).
+ * All replacement rows are read from the table as it was before the call, so sources and
+ * targets may overlap (a swap is two one-to-one calls' worth in one).  backup (device,
+ * [n_s,F], may be NULL) receives the old source rows; writing them back undoes the edit.
+ * src_ids, tgt_ids: host memory, at most 64 tokens each.  The mean is taken in fp32 and
+ * rounded to the table's dtype.  When n_s < n_t the caller chooses which target tokens to
+ * keep (the paper selects them by hand) and passes that subset.  Waits for `stream` once
+ * (the index upload is synchronous); the row kernels run on `stream`.  Applies to one
+ * table: call it for every STEM layer's table to edit a model. */
+stem_status stem_edit_rows(stem_ctx* ctx, void* E, const int32_t* src_ids, int64_t n_s, const int32_t* tgt_ids,
+                           int64_t n_t, int mode, int32_t pad_id, void* backup, void* stream);
+
 /* ---- measurement aid ------------------------------------------------------------ */
 
 /* With profiling on, every kernel launch of the context is bracketed by HIP events on

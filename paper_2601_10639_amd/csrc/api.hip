@@ -85,6 +85,7 @@ void release(stem_ctx* c) {
   if (c->pack_pinned) (void)hipHostFree(c->pack_pinned);
   free(c->slot);
   free(c->cache_id_in_slot); free(c->cache_slot_of); free(c->cache_freq);
+  (void)hipFree(c->edit_idx_dev); (void)hipFree(c->edit_rep_dev);
   if (c->inst_pinned) (void)hipHostFree(c->inst_pinned);
   (void)hipFree(c->inst_dev);
   if (c->side) (void)hipStreamDestroy(c->side);
@@ -843,6 +844,66 @@ stem_status stem_prefetch_rows_cached(stem_ctx* c, const void* E_host, const int
     HIP_TRY(c, stem_copy_rows_kernel(c, E_dev, c->inst_dev, c->inst_dev + c->max_tokens, n_inst, (int64_t)row_bytes,
                                      E_dev, c->side));
   }
+  return STEM_OK;
+}
+
+// ---- knowledge editing: rows of a source entity's tokens replaced by a target entity's -----------
+
+stem_status stem_edit_rows(stem_ctx* c, void* E, const int32_t* src_ids_host, int64_t n_s,
+                           const int32_t* tgt_ids_host, int64_t n_t, int mode, int32_t pad_id, void* backup,
+                           void* stream) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  if (!E || !src_ids_host || !tgt_ids_host)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_edit_rows: null pointer argument");
+  if (n_s < 1 || n_t < 1 || n_s > STEM_EDIT_MAX_TOKENS || n_t > STEM_EDIT_MAX_TOKENS)
+    return fail(c, STEM_ERR_SHAPE, "stem_edit_rows: n_s = %lld, n_t = %lld must lie in [1, %d]", (long long)n_s,
+                (long long)n_t, STEM_EDIT_MAX_TOKENS);
+  const int V = c->desc.vocab;
+  int32_t idx[3 * STEM_EDIT_MAX_TOKENS];
+  int32_t* src = idx;
+  int32_t* pick = idx + STEM_EDIT_MAX_TOKENS;
+  int32_t* tgt = idx + 2 * STEM_EDIT_MAX_TOKENS;
+  for (int64_t j = 0; j < n_s; ++j) {
+    if ((uint32_t)src_ids_host[j] >= (uint32_t)V)
+      return fail(c, STEM_ERR_ID_RANGE, "stem_edit_rows: source id %d is outside [0, %d)", src_ids_host[j], V);
+    src[j] = src_ids_host[j];
+  }
+  for (int64_t k = 0; k < n_t; ++k) {
+    if ((uint32_t)tgt_ids_host[k] >= (uint32_t)V)
+      return fail(c, STEM_ERR_ID_RANGE, "stem_edit_rows: target id %d is outside [0, %d)", tgt_ids_host[k], V);
+    tgt[k] = tgt_ids_host[k];
+  }
+  // which target token's row each source position receives (-1 = the mean of all target rows)
+  if (mode == STEM_EDIT_REPLACE) {
+    if (n_s != n_t) return fail(c, STEM_ERR_SHAPE, "stem_edit_rows: one-to-one replacement needs n_s == n_t");
+    for (int64_t j = 0; j < n_s; ++j) pick[j] = tgt[j];
+  } else if (mode == STEM_EDIT_PAD_LEFT || mode == STEM_EDIT_COPY) {
+    if (n_s < n_t) return fail(c, STEM_ERR_SHAPE, "stem_edit_rows: padding and copying need n_s >= n_t");
+    if (mode == STEM_EDIT_PAD_LEFT) {
+      if ((uint32_t)pad_id >= (uint32_t)V)
+        return fail(c, STEM_ERR_ID_RANGE, "stem_edit_rows: pad id %d is outside [0, %d)", pad_id, V);
+      for (int64_t j = 0; j < n_s; ++j) pick[j] = j < n_s - n_t ? pad_id : tgt[j - (n_s - n_t)];
+    } else {   // every target token floor(n_s / n_t) times, the last one as often as it takes
+      const int64_t r = n_s / n_t;
+      for (int64_t j = 0; j < n_s; ++j) pick[j] = tgt[std::min<int64_t>(j / r, n_t - 1)];
+    }
+  } else if (mode == STEM_EDIT_AVERAGE) {
+    for (int64_t j = 0; j < n_s; ++j) pick[j] = -1;
+  } else {
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_edit_rows: unknown mode %d", mode);
+  }
+  HIP_TRY(c, hipSetDevice(c->device));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!c->edit_idx_dev) {
+    HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&c->edit_idx_dev), sizeof(idx)));
+    HIP_TRY(c, hipMalloc(&c->edit_rep_dev, (size_t)STEM_EDIT_MAX_TOKENS * c->desc.d_ff * esize(c)));
+  }
+  // the index lists are small and this call is rare: a synchronous upload keeps the host array on the stack
+  HIP_TRY(c, hipStreamSynchronize(s));
+  HIP_TRY(c, hipMemcpy(c->edit_idx_dev, idx, sizeof(idx), hipMemcpyHostToDevice));
+  HIP_TRY(c, stem_edit_launch(c, c->desc.dtype == STEM_BF16, E, c->edit_idx_dev, c->edit_idx_dev + STEM_EDIT_MAX_TOKENS,
+                              c->edit_idx_dev + 2 * STEM_EDIT_MAX_TOKENS, (int)n_s, (int)n_t, c->desc.d_ff,
+                              c->edit_rep_dev, backup, s));
   return STEM_OK;
 }
 

@@ -36,6 +36,7 @@ enum StemKernelId {
 
 #define STEM_MAX_PROF_EVENTS 8192
 #define STEM_PF_MAX_CHUNKS 16
+#define STEM_EDIT_MAX_TOKENS 64
 #define STEM_PF_CHUNK_TILES 256     // one round of 256x256 down-product tiles per chunk (measured better than 224 and 512)
 
 struct stem_ctx {
@@ -87,6 +88,10 @@ struct stem_ctx {
   uint32_t* cache_freq;      // host [V]: token occurrences seen so far
   int32_t* inst_pinned;      // pinned host [2 * max_tokens]: promoted rows (staging row, then cache slot)
   int32_t* inst_dev;         // device [2 * max_tokens]
+
+  // knowledge editing: device scratch for up to STEM_EDIT_MAX_TOKENS source / target tokens
+  int32_t* edit_idx_dev;     // [3 * STEM_EDIT_MAX_TOKENS]: source rows, picked rows, target rows
+  void* edit_rep_dev;        // [STEM_EDIT_MAX_TOKENS, F] replacement rows
 
   // profiling
   int prof_on;
@@ -200,3 +205,9 @@ hipError_t stem_adamw(stem_ctx* ctx, int is_bf16, const int32_t* uniq_ids, const
 // E_compact[dst_slot[k]] = E_host[src_row[k]] for k in [0, n)
 hipError_t stem_copy_rows_kernel(stem_ctx* ctx, const void* E_host, const int32_t* src_row, const int32_t* dst_slot,
                                  int64_t n, int64_t row_bytes, void* E_compact, hipStream_t s);
+
+// ---- knowledge editing (edit.hip) ----------------------------------------------------------
+// rows E[src[j]] <- (pick[j] >= 0 ? old E[pick[j]] : mean of the old rows E[tgt[0..n_t)]); the old
+// source rows go to backup (may be null).  rep: [n_s, F] scratch in the table's dtype.
+hipError_t stem_edit_launch(stem_ctx* ctx, int is_bf16, void* E, const int32_t* src_dev, const int32_t* pick_dev,
+                            const int32_t* tgt_dev, int n_s, int n_t, int F, void* rep, void* backup, hipStream_t s);

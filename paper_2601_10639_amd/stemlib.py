@@ -24,7 +24,7 @@ SYMBOLS = [
     "stem_ffn_forward", "stem_ffn_backward", "stem_ffn_up_forward", "stem_ffn_up_backward",
     "stem_embed_grad", "stem_embed_sparse_adamw",
     "stem_prefetch_rows", "stem_cache_init", "stem_prefetch_rows_cached", "stem_cache_state",
-    "stem_profile_enable", "stem_profile_kernels", "stem_profile_read",
+    "stem_edit_rows", "stem_profile_enable", "stem_profile_kernels", "stem_profile_read",
     "stem_profile_reset",
 ]
 
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.stem_prefetch_rows_cached.restype = i32
         L.stem_cache_state.argtypes = [vp, vp, i64]
         L.stem_cache_state.restype = i32
+        L.stem_edit_rows.argtypes = [vp, vp, vp, i64, vp, i64, i32, i32, vp, vp]
+        L.stem_edit_rows.restype = i32
         L.stem_profile_enable.argtypes = [vp, i32]
         L.stem_profile_enable.restype = i32
         L.stem_profile_kernels.argtypes = []
@@ -308,6 +310,18 @@ def stem_cache_state(ctx: StemCtx, n_slots: int):
     _check(ctx, lib().stem_cache_state(ctx.handle, _ptr(out, torch.int32, cuda=False, name="out"), n_slots),
            "stem_cache_state")
     return out
+
+
+STEM_EDIT_REPLACE, STEM_EDIT_PAD_LEFT, STEM_EDIT_COPY, STEM_EDIT_AVERAGE = 0, 1, 2, 3
+
+
+def stem_edit_rows(ctx: StemCtx, E, src_ids, tgt_ids, mode: int, pad_id: int = 0, backup=None, stream=None):
+    """src_ids, tgt_ids: sequences of token ids (host).  E: the layer's table on the device."""
+    src = (ctypes.c_int32 * len(src_ids))(*[int(t) for t in src_ids])
+    tgt = (ctypes.c_int32 * len(tgt_ids))(*[int(t) for t in tgt_ids])
+    st = lib().stem_edit_rows(ctx.handle, _ptr(E, ctx.torch_dtype, name="E"), src, len(src_ids), tgt, len(tgt_ids),
+                              mode, pad_id, _ptr(backup, ctx.torch_dtype, name="backup"), _stream(stream))
+    _check(ctx, st, "stem_edit_rows")
 
 
 def stem_profile_enable(ctx: StemCtx, on: bool):

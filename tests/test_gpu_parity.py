@@ -233,6 +233,56 @@ def test_weight_gradient_accumulate_flag(T):
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_knowledge_edit_row_operations(dtype):
+    """One-to-one, left-padded, copied and averaged replacement of a source entity's rows: copied
+    rows bit for bit, the mean within one rounding of the table's dtype; backup restores the table."""
+    V, F = 200, 320
+    s = inputs.StemShape("edit", 64, F, V, 1, 8, dtype)
+    dt = inputs.torch_dtype(dtype)
+    ctx = Hn.make_ctx(s, 8)
+    E0 = inputs.normal((V, F), 0.02, 51, dt, DEV)
+    E64 = inputs.to_f64(E0)
+    rnd = O.bf16_round if dtype == "bf16" else (lambda a: a.astype(np.float32).astype(np.float64))
+    cases = [([3, 7, 9], [7, 5, 3], L.STEM_EDIT_REPLACE, O.EDIT_REPLACE),        # overlapping: 3 <-> 7 and 9 <- 3
+             ([3, 7, 8, 1], [7, 5], L.STEM_EDIT_PAD_LEFT, O.EDIT_PAD_LEFT),
+             ([3, 7, 8, 1, 6], [7, 5], L.STEM_EDIT_COPY, O.EDIT_COPY),
+             ([3, 7, 8, 1, 6, 2, 0], [9, 5, 11], L.STEM_EDIT_COPY, O.EDIT_COPY),
+             ([3, 7], [5, 6, 11, 150, 199], L.STEM_EDIT_AVERAGE, O.EDIT_AVERAGE),
+             ([4], [4], L.STEM_EDIT_AVERAGE, O.EDIT_AVERAGE)]
+    for src, tgt, mode, omode in cases:
+        E = E0.clone()
+        backup = torch.empty(len(src), F, dtype=dt, device=DEV)
+        L.stem_edit_rows(ctx, E, src, tgt, mode, pad_id=13, backup=backup)
+        torch.cuda.synchronize()
+        want, want_backup = O.edit_rows(E64, src, tgt, omode, pad_id=13, round_row=rnd)
+        got = inputs.to_f64(E)
+        np.testing.assert_array_equal(inputs.to_f64(backup), want_backup)
+        if omode == O.EDIT_AVERAGE:
+            ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22
+            assert np.abs(got - want).max() <= ulp * np.abs(want).max()
+            rest = np.setdiff1d(np.arange(V), src)
+            np.testing.assert_array_equal(got[rest], E64[rest])
+        else:
+            np.testing.assert_array_equal(got, want)
+        E[torch.tensor(src, device=DEV)] = backup          # undo
+        assert torch.equal(E.view(torch.int16 if dtype == "bf16" else torch.int32),
+                           E0.view(torch.int16 if dtype == "bf16" else torch.int32))
+    E = E0.clone()
+    for bad, status in ((([1, 2], [3, 4, 5], L.STEM_EDIT_COPY), L.STEM_ERR_SHAPE),
+                        (([1, 2], [3], L.STEM_EDIT_REPLACE), L.STEM_ERR_SHAPE),
+                        (([1, V], [3, 4], L.STEM_EDIT_REPLACE), L.STEM_ERR_ID_RANGE),
+                        (([1, 2], [3, -1], L.STEM_EDIT_REPLACE), L.STEM_ERR_ID_RANGE),
+                        (([1], [2], 9), L.STEM_ERR_INVALID_ARG),
+                        ((list(range(65)), [2], L.STEM_EDIT_AVERAGE), L.STEM_ERR_SHAPE)):
+        with pytest.raises(L.StemError) as e:
+            L.stem_edit_rows(ctx, E, *bad)
+        assert e.value.status == status
+    torch.cuda.synchronize()
+    assert torch.equal(E, E0)   # a rejected call changes nothing
+    ctx.close()
+
+
 def test_edge_cases_and_error_reporting():
     s = inputs.SHAPES["C1"]
     inp = inputs.layer_inputs(s, 13, device=DEV)
