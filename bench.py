@@ -38,6 +38,7 @@ def main() -> int:
     ap.add_argument("--ids", default="zipf", choices=["zipf", "uniform"], help="id distribution for C5")
     ap.add_argument("--cache-slots", type=int, default=0,
                     help="C5: device-resident LFU cache of this many rows (0 = none); ten batches warm it first")
+    ap.add_argument("--graph", action="store_true", help="C4: capture the 16-layer step in a HIP graph and replay it")
     ap.add_argument("--host-state", action="store_true",
                     help="C2/C3: training step with the table, its fp32 master and the AdamW moments in pinned host "
                          "memory (rows prefetched, optimiser straight on the host-resident state)")
@@ -265,6 +266,18 @@ def bench_decode(args, shape, dev):
             L.stem_ffn_forward(ctx, x, ids, Wg[l], Wd[l], E[l], y)
             x.add_(y)
 
+    eager_step = step
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            eager_step()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                eager_step()
+        torch.cuda.synchronize()
+        step = graph.replay
     steps = max(args.steps, 50)
     med, p10, p90 = _median_ms(step, steps, max(args.warmup, 10))
     for _ in range(args.warmup):
@@ -279,7 +292,7 @@ def bench_decode(args, shape, dev):
     L.stem_profile_enable(ctx, True)
     L.stem_profile_reset(ctx)
     for _ in range(10):
-        step()
+        eager_step()
     prof = L.stem_profile_read(ctx)
     L.stem_profile_enable(ctx, False)
     kernels = {k: {"avg_ms": round(v[0] / v[1], 5), "launches": v[1]} for k, v in prof.items()}
@@ -293,7 +306,7 @@ def bench_decode(args, shape, dev):
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "layers": n_layers,
-                   "n_uniq": U, "ids": "Zipf(s=1.1)", "step": "16 x (forward + residual add)"},
+                   "n_uniq": U, "ids": "Zipf(s=1.1)", "step": "16 x (forward + residual add)", "hip_graph": bool(args.graph)},
         "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4),
                        "back_to_back": round(ms, 4), "kernels_only": round(kern_ms, 4)},
         "roofline": {"bound": "hbm", "kernel": "decode step (all kernels)",

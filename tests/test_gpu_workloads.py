@@ -129,6 +129,52 @@ def test_c4_decode_chain_sixteen_layers():
     ctx.close()
 
 
+def test_decode_forward_can_be_captured_in_a_hip_graph():
+    """A four-layer decode chain captured once and replayed five times, with eager work and
+    synchronisations between the replays; every replay must equal the eager result bit for bit."""
+    shape = inputs.StemShape("decode-graph", 512, 1024, 2000, 64, 1, "bf16")
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    ids = torch.from_numpy(inputs.zipf_ids(T, V, seed=33)).to(DEV)
+    ctx = Hn.make_ctx(shape, T)
+    layers = [(inputs.normal((F, d), 0.02, 300 + 3 * l, torch.bfloat16, DEV),
+               inputs.normal((d, F), 0.02, 301 + 3 * l, torch.bfloat16, DEV),
+               inputs.normal((V, F), 0.02, 302 + 3 * l, torch.bfloat16, DEV)) for l in range(4)]
+    x0 = inputs.normal((T, d), 1.0, 34, torch.bfloat16, DEV)
+    x = x0.clone()
+    y = torch.empty_like(x)
+
+    def chain():
+        x.copy_(x0)
+        for Wg, Wd, E in layers:
+            L.stem_ffn_forward(ctx, x, ids, Wg, Wd, E, y)
+            x.add_(y)
+
+    chain()
+    torch.cuda.synchronize()
+    want = x.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        chain()                       # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            chain()
+    torch.cuda.synchronize()
+    for r in range(5):
+        x.zero_()
+        y.fill_(3.0)                  # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(x, want), r
+        chain()                       # and an eager run in between
+        torch.cuda.synchronize()
+        assert torch.equal(x, want)
+    L.stem_sync_status(ctx)
+    ctx.close()
+
+
 def _prefetch_case(shape, T, ids_np, seed, mode=None):
     d, F, V = shape.d_model, shape.d_ff, shape.vocab
     dt = inputs.torch_dtype(shape.dtype)
