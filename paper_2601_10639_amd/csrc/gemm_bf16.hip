@@ -121,7 +121,8 @@ struct LoaderMC {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t lo = pick(st[2 * j], q), hi = pick(st[2 * j + 1], q);
-      w[j] = (r & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+      // one byte permute: the two high (odd r) or the two low (even r) halves of hi:lo
+      w[j] = __builtin_amdgcn_perm(hi, lo, (r & 1) ? 0x07060302u : 0x05040100u);
     }
     *reinterpret_cast<uint4*>(tile + lds_off(rb * 8 + r, kb)) = make_uint4(w[0], w[1], w[2], w[3]);
   }
