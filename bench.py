@@ -46,7 +46,7 @@ def main() -> int:
                     help="stem: the STEM layer (the headline); dense: SwiGLU FFN with an up projection and no table; "
                          "additive: up projection plus table (C2, C3 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()

@@ -103,6 +103,28 @@ def stem_dagger_forward(x, ids, W_gate, W_up, W_down, E):
 
 
 # ----------------------------------------------------------------------------
+# cost model (System Implementation, theoretical-efficiency table and "Training efficiency")
+# ----------------------------------------------------------------------------
+def train_flops_per_layer(B: int, L: int, d: int, d_ff: int, stem: bool) -> int:
+    """Per-layer training FLOPs in the paper's units (forward + backward, element-wise work and
+    biases ignored): attention 4 L d^2 + 2 L^2 d per sequence, FFN 3 L d d_ff for the dense
+    SwiGLU layer and 2 L d d_ff when the up projection is replaced by the table."""
+    return B * (4 * L * d * d + 2 * L * L * d + (2 if stem else 3) * L * d * d_ff)
+
+
+def train_saving_fraction(d: int, d_ff: int, L: int) -> float:
+    """(F_base - F_stem) / F_base = d_ff / (4 d + 2 L + 3 d_ff)."""
+    base = train_flops_per_layer(1, L, d, d_ff, stem=False)
+    return (base - train_flops_per_layer(1, L, d, d_ff, stem=True)) / base
+
+
+def ffn_macs_per_token(d: int, d_ff: int, stem: bool) -> int:
+    """Multiply-adds of one token's FFN forward: three d x d_ff projections, two with the table
+    (efficiency table, prefill / training row, per token and without the element-wise term)."""
+    return (2 if stem else 3) * d * d_ff
+
+
+# ----------------------------------------------------------------------------
 # backward  (chain rule of the STEM equation; not printed in the paper)
 # ----------------------------------------------------------------------------
 def ffn_backward(dy, x, ids, W_gate, W_down, E):

@@ -374,6 +374,29 @@ def test_dedup_remap_matches_numpy_unique():
     np.testing.assert_array_equal(uniq[remap], ids)
 
 
+def test_cost_model_reproduces_the_printed_saving_fractions():
+    # golden values: percentages the paper prints for five published model configurations
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "train_saving_fractions.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                name, d, dff, L, pct, status = line.split()
+                rows.append((name, int(d), int(dff), int(L), float(pct), status))
+    assert len(rows) == 5
+    for name, d, dff, L, pct, status in rows:
+        got = 100.0 * O.train_saving_fraction(d, dff, L)
+        assert abs(got - 100.0 * dff / (4 * d + 2 * L + 3 * dff)) < 1e-9          # the closed form
+        if status == "ok":
+            assert abs(got - pct) <= 0.05, (name, got, pct)
+        else:   # the one printed value the paper's own formula does not give
+            assert round(got, 1) == 22.3 and pct == 22.8
+    # the FFN part alone: exactly one third fewer multiply-adds, whatever the widths
+    for d, dff in ((1024, 4096), (2048, 8192), (1536, 8960)):
+        assert 3 * O.ffn_macs_per_token(d, dff, True) == 2 * O.ffn_macs_per_token(d, dff, False)
+        assert O.train_flops_per_layer(3, 7, d, dff, False) - O.train_flops_per_layer(3, 7, d, dff, True) == 3 * 7 * d * dff
+
+
 def test_lfu_row_cache_serves_right_rows_and_keeps_the_most_frequent():
     # simulate the device buffer [cache slots | staging] and check every token finds its row;
     # check the LFU property after every batch; check the hit rate on a Zipf stream
