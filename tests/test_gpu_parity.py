@@ -207,6 +207,30 @@ def test_segmented_sum_is_bit_reproducible_and_conserves_column_sums():
     ctx.close()
 
 
+@pytest.mark.parametrize("T", [300, 700])   # the few-row and the 256x256-tile forward kernels
+def test_bf16_saturated_gate_activations_stay_finite(T):
+    """Pre-activations far beyond the range where exp() overflows in fp32 (|g| up to ~200): SiLU and
+    its derivative must come out as their limits (0 or g, 0 or 1), never NaN or inf."""
+    s = inputs.StemShape("saturated", 192, 320, 400, 1, T, "bf16")
+    inp = inputs.layer_inputs(s, seed=19, device=DEV, tokens=T)
+    inp["x"] = (inp["x"].float() * 150.0).to(torch.bfloat16)
+    ctx = Hn.make_ctx(s, T)
+    out = Hn.hip_forward_backward(ctx, inp)
+    L.stem_sync_status(ctx)
+    f64 = {k: inputs.to_f64(v) for k, v in inp.items() if k != "ids"}
+    ids = inp["ids"].cpu().numpy()
+    y, fw = O.ffn_forward(f64["x"], ids, f64["W_gate"], f64["W_down"], f64["E"])
+    bw = O.ffn_backward(f64["dy"], f64["x"], ids, f64["W_gate"], f64["W_down"], f64["E"])
+    assert np.abs(fw["g"]).max() > 120.0          # the case is what it claims to be
+    for k in ("y", "G", "H", "dx", "dU", "dW_gate", "dW_down"):
+        assert bool(torch.isfinite(out[k].float()).all()), k
+    errs = {"y": Hn.max_rel(out["y"].float().cpu(), y), "H": Hn.max_rel(out["H"].float().cpu(), fw["h"]),
+            "dx": Hn.max_rel(out["dx"].float().cpu(), bw["dx"]), "dU": Hn.max_rel(out["dU"].float().cpu(), bw["dU"]),
+            "dW_gate": Hn.max_rel(out["dW_gate"].cpu(), bw["dW_gate"])}
+    assert all(v <= Hn.TOL["bf16"] for v in errs.values()), errs
+    ctx.close()
+
+
 def test_whole_backward_is_bit_reproducible():
     s = inputs.StemShape("det2", 128, 256, 400, 1, 700, "bf16")
     inp = inputs.layer_inputs(s, 11, device=DEV, tokens=700)
