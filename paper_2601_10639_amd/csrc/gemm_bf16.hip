@@ -164,7 +164,11 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int ntm, int ntn, i
 
 template <int LA, int LB, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
-  __shared__ __attribute__((aligned(16))) char smem[2 * STAGE_BYTES];
+  // (KC,KC) products keep their operand tiles in a ring of five 32 KB slots (A and B tiles of
+  // successive K tiles in turn) instead of two 64 KB stages: see the main loop.
+  constexpr bool RING = (LA == OP_KC && LB == OP_KC);
+  constexpr int SMEM_BYTES = RING ? 5 * TILE_BYTES : 2 * STAGE_BYTES;
+  __shared__ __attribute__((aligned(16))) char smem[SMEM_BYTES];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -291,6 +295,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   };
 
   const int nk = nk1 + ((LA == OP_KC && LB == OP_KC && p.A2) ? (p.K2 + BK - 1) / BK : 0);
+  // The gate epilogue reads one gathered table row per output row.  A few K tiles before the end
+  // of the main loop each lane touches the 128-byte lines its wavefront will need, so that they
+  // travel from HBM to L2 under the MFMA work instead of in a burst when all workgroups reach
+  // their epilogues together.  (Measured: 0.05 ms off the gate product at d=2048, F=8192; the dH
+  // product gains nothing from the same trick - its lines are evicted again before the epilogue,
+  // FETCH_SIZE grows by 30 % - so it does not touch.)
+  // The touching loads return asynchronously into their destination registers, so these stay
+  // reserved (never reused by the compiler) until the wait that follows the main loop.
+  constexpr bool TOUCH = (EPI == EPI_GATE);
+  uint32_t touched[4] = {0, 0, 0, 0};
+  auto touch_epilogue_inputs = [&]() {
+    if (!TOUCH) return;
+    const int ncol = n0 + wn * 128;
+    const int col = ncol < p.N ? ncol : 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int m = m0 + wm * 128 + h * 64 + lane;
+      const int mc = m < p.M ? m : p.M - 1;
+      int id = p.ids[mc];
+      if ((unsigned)id >= (unsigned)p.E_rows) id = id < 0 ? 0 : p.E_rows - 1;  // reported by the epilogue
+      const bf16_t* e = p.E + (size_t)id * p.N + col;
+      asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
+                   : "=&v"(touched[2 * h]), "=&v"(touched[2 * h + 1]) : "v"(e) : "memory");
+    }
+  };
+  const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
+  bf16x8_t xa[4], xb[4], ya[4], yb[4];
+  if constexpr (!RING) {
   // ---- prologue: tile 0 into stage 0 -------------------------------------------------
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
@@ -305,7 +337,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   }
   advance();
   __syncthreads();
-  bf16x8_t xa[4], xb[4], ya[4], yb[4];
 #pragma unroll
   for (int q = 0; q < 8; ++q) rfrag1(0, 0, q, xa, xb);
 #pragma unroll
@@ -350,38 +381,114 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // The gate epilogue reads one gathered table row per output row.  A few K tiles before the end
-  // of the main loop each lane touches the 128-byte lines its wavefront will need, so that they
-  // travel from HBM to L2 under the MFMA work instead of in a burst when all workgroups reach
-  // their epilogues together.  (Measured: 0.05 ms off the gate product at d=2048, F=8192; the dH
-  // product gains nothing from the same trick - its lines are evicted again before the epilogue,
-  // FETCH_SIZE grows by 30 % - so it does not touch.)
-  // The touching loads return asynchronously into their destination registers, so these stay
-  // reserved (never reused by the compiler) until the wait that follows the main loop.
-  constexpr bool TOUCH = (EPI == EPI_GATE);
-  uint32_t touched[4] = {0, 0, 0, 0};
-  auto touch_epilogue_inputs = [&]() {
-    if (!TOUCH) return;
-    const int ncol = n0 + wn * 128;
-    const int col = ncol < p.N ? ncol : 0;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int m = m0 + wm * 128 + h * 64 + lane;
-      const int mc = m < p.M ? m : p.M - 1;
-      int id = p.ids[mc];
-      if ((unsigned)id >= (unsigned)p.E_rows) id = id < 0 ? 0 : p.E_rows - 1;  // reported by the epilogue
-      const bf16_t* e = p.E + (size_t)id * p.N + col;
-      asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
-                   : "=&v"(touched[2 * h]), "=&v"(touched[2 * h + 1]) : "v"(e) : "memory");
-    }
-  };
-  const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
   for (int kt = 0; kt + 1 < nk; kt += 2) {
     if (TOUCH && kt == touch_at) touch_epilogue_inputs();
     iteration(0);
     iteration(1);
   }
   if (nk & 1) iteration(0);
+  } else {
+  // ---- (KC,KC): ring of five 32 KB slots ------------------------------------------------------
+  // Operand tiles alternate through the slots: A of K tile t in slot 2t mod 5, B in slot 2t+1 mod 5.
+  // While K tile t is multiplied, A(t+1), B(t+1) are landing or landed and A(t+2) is requested
+  // during the first two k-steps into the slot B(t-1) left; after the barrier that ends the reads
+  // of K tile t, B(t+2) is requested into A(t)'s slot.  Every request thus has a whole K tile's
+  // time (B) or more (A) before it is waited for, a request is always in flight across the
+  // barrier, and the wait before the barrier leaves the youngest 8 loads pending.  With two 64 KB
+  // stages the loads of a K tile were requested and drained within that tile's own time, and the
+  // direct-load stream alone (no MFMA, no fragment reads) took as long as the whole kernel.
+  uint32_t ra_addr[3][4], rb_addr[3][4];   // [slot pair][k-step]; the odd slot of a pair is an immediate away
+#pragma unroll
+  for (int pr = 0; pr < 3; ++pr)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ (frow >> 1)) & 7) << 4);
+      ra_addr[pr][ks] = (uint32_t)(pr * 2 * TILE_BYTES + (wm * 128 + frow) * 128) + sw;
+      rb_addr[pr][ks] = (uint32_t)(pr * 2 * TILE_BYTES + (wn * 128 + frow) * 128) + sw;
+    }
+  auto rfrag_ring = [&](int sa, int sb, int ks, int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
+    constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
+    constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
+    if (isA[q])
+      fa[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + ra_addr[sa >> 1][ks] + (sa & 1) * TILE_BYTES + idx[q] * 4096);
+    else
+      fb[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + rb_addr[sb >> 1][ks] + (sb & 1) * TILE_BYTES + idx[q] * 4096);
+  };
+  int a_to_switch = p.A2 ? nk1 : -1, b_to_switch = a_to_switch;
+  auto next_A = [&]() {
+    if (--a_to_switch == 0) ka.win.set(p.A2, (int64_t)p.M * p.lda * 2); else ka.next_tile();
+  };
+  auto next_B = [&]() {
+    if (--b_to_switch == 0) kb_.win.set(p.B2, (int64_t)p.N * p.ldb * 2); else kb_.next_tile();
+  };
+  // prologue: A0, B0, A1, B1 into slots 0..3
+#pragma unroll
+  for (int h = 0; h < 4; ++h) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      if (h & 1) kb_.issue(q, smem + h * TILE_BYTES, wave); else ka.issue(q, smem + h * TILE_BYTES, wave);
+    }
+    if (h & 1) next_B(); else next_A();
+  }
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 8; ++q) rfrag_ring(0, 1, 0, q, xa, xb);
+  // K tile t with t mod 5 == tmod (all slot numbers are compile-time constants)
+  auto ring_iteration = [&](const int tmod) __attribute__((always_inline)) {
+    const int sa = (2 * tmod) % 5, sb = (2 * tmod + 1) % 5;        // this tile
+    const int na = (2 * tmod + 2) % 5, nb = (2 * tmod + 3) % 5;    // the next tile
+    const int ia = (2 * tmod + 4) % 5;                             // receives A(t+2); B(t+2) goes to sa
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_ring(sa, sb, 1, q, ya, yb);
+      if (q < 4) ka.issue(q, smem + ia * TILE_BYTES, wave);
+      mma2(q, xa, xb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_ring(sa, sb, 2, q, xa, xb);
+      if (q < 4) ka.issue(4 + q, smem + ia * TILE_BYTES, wave);
+      mma2(q, ya, yb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    next_A();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_ring(sa, sb, 3, q, ya, yb);
+      mma2(q, xa, xb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // A(t+1) and B(t+1) have landed (only the 8 loads of A(t+2) may be pending) and nobody reads
+    // this tile's slots any more
+    asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_ring(na, nb, 0, q, xa, xb);
+      kb_.issue(q, smem + sa * TILE_BYTES, wave);
+      mma2(q, ya, yb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    next_B();
+  };
+  int kt = 0;
+  for (; kt + 5 <= nk; kt += 5) {
+    if (TOUCH && kt <= touch_at && touch_at < kt + 5) touch_epilogue_inputs();
+    ring_iteration(0);
+    ring_iteration(1);
+    ring_iteration(2);
+    ring_iteration(3);
+    ring_iteration(4);
+  }
+  if (TOUCH && kt <= touch_at) touch_epilogue_inputs();
+  if (kt < nk) ring_iteration(0);
+  if (kt + 1 < nk) ring_iteration(1);
+  if (kt + 2 < nk) ring_iteration(2);
+  if (kt + 3 < nk) ring_iteration(3);
+  }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (TOUCH)   // end of the touched registers' reservation
     asm volatile("" ::"v"(touched[0]), "v"(touched[1]), "v"(touched[2]), "v"(touched[3]));
