@@ -3,7 +3,9 @@
 //
 // One kernel template computes  C[m,n] = sum_k Aop[m,k] * Bop[n,k]  on a 256x256
 // output tile per workgroup: 4 wavefronts, each a 128x128 quadrant held as 4x4
-// accumulators of v_mfma_f32_32x32x16_bf16, K stepped by 64 through two LDS stages.
+// accumulators of v_mfma_f32_32x32x16_bf16, K stepped by 64 through five 32 KB LDS
+// slots (one operand tile each), so that every global request is made more than a
+// whole K tile before its data is needed.
 //
 // Operands.  "KC" = stored [rows,K] with K contiguous: tiles go global -> LDS directly
 // (buffer_load ... lds, 16 bytes per lane, whole 128-byte lines per row; half lines were
@@ -19,12 +21,13 @@
 //
 // Schedule.  One iteration = one K tile = 4 k-steps of 16 MFMAs.  Fragments are double
 // buffered in registers: while the MFMAs of k-step s run, the 8 fragment reads of step
-// s+1 are issued between them.  The loads of the next tile are spread over the k-steps
+// s+1 are issued between them.  The loads of later tiles are spread over the k-steps
 // (a vector-memory instruction blocks the issuing wavefront for tens of cycles, during
 // which its MFMA queue drains, so they are never issued back to back).  The single
 // barrier per iteration sits before the last k-step, so that step overlaps the first
-// fragment reads of the next stage.  The loop is unrolled by two so that every LDS
-// address is a loop-invariant register plus an immediate.
+// fragment reads of the next tile, and the wait before it leaves the youngest requests
+// in flight.  The loop is unrolled over the slot rotation (5 or 6 K tiles) so that every
+// LDS address is a loop-invariant register plus an immediate.
 //
 // Epilogue.  The MFMA is issued with the N-side fragment as its row operand, so a lane
 // holds, for one m, groups of 4 consecutive n.  Each wavefront stages its accumulators
@@ -36,6 +39,7 @@
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
@@ -46,6 +50,9 @@ constexpr int TILE_BYTES = 256 * BK * 2;  // one operand tile in LDS
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;
 constexpr uint32_t OOB = 0x80000000u;  // a buffer offset beyond any operand: reads as zero
 
+__device__ __forceinline__ uint32_t lds_addr(const char* p) {   // p points into LDS
+  return (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<char*>(p);
+}
 __device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
   return (uint32_t)(row * 128 + (((chunk ^ (row >> 1)) & 7) << 4));
 }
@@ -98,33 +105,42 @@ struct LoaderMC {
   uint32_t off0;
   uint32_t ld2;
   Window win;
-  uint4 st[8];
+  uint32_t wbase[4];   // offset within a tile of this thread's rows rb*8 + 2j; row 2j+1 is 128 bytes on
+  uint4 st[2][8];   // two tiles' worth of loads may be in flight (the ring schedule); else only set 0
   __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int K, int row0, int tid) {
     win.set(p, (int64_t)K * ld * 2);
     ld2 = (uint32_t)ld * 2;
     const int kb = tid & 7, rb = tid >> 3;
     off0 = (row0 + rb * 8) < rows ? (uint32_t)(((int64_t)kb * 8 * ld + row0 + rb * 8) * 2) : OOB;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wbase[j] = lds_off(rb * 8 + 2 * j, kb);
   }
-  __device__ __forceinline__ void issue(int kk) {
+  __device__ __forceinline__ void issue(int kk, int set = 0) {
     const uint32_t o = off0 == OOB ? OOB : off0 + kk * ld2;
-    st[kk] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(win.rsrc(), o, 0, 0));
+    st[set][kk] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(win.rsrc(), o, 0, 0));
   }
   __device__ __forceinline__ void next_tile() { win.advance((int)(BK * ld2)); }
   static __device__ __forceinline__ uint32_t pick(const uint4& v, int q) {
     return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
   }
-  // rows r of this thread's block, transposed so that k runs along the 16-byte chunk
-  __device__ __forceinline__ void commit(int r, char* tile, int tid) const {
-    const int kb = tid & 7, rb = tid >> 3;
+  // rows r of this thread's block, transposed so that k runs along the 16-byte chunk, to the
+  // tile at LDS address `tile`.  The store is written as assembly on purpose: for a compiler-made
+  // LDS store the compiler first waits for every outstanding direct-to-LDS load (it cannot tell
+  // that those go to other slots), which would drain the other operand's requests in the middle
+  // of the K tile.  The callers order these stores themselves (lgkmcnt(0) and a barrier before
+  // any wavefront reads the tile).
+  __device__ __forceinline__ void commit(int r, uint32_t tile, int set = 0) const {
     const int q = r >> 1;
-    uint32_t w[4];
+    u32x4_t w;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t lo = pick(st[2 * j], q), hi = pick(st[2 * j + 1], q);
+      const uint32_t lo = pick(st[set][2 * j], q), hi = pick(st[set][2 * j + 1], q);
       // one byte permute: the two high (odd r) or the two low (even r) halves of hi:lo
       w[j] = __builtin_amdgcn_perm(hi, lo, (r & 1) ? 0x07060302u : 0x05040100u);
     }
-    *reinterpret_cast<uint4*>(tile + lds_off(rb * 8 + r, kb)) = make_uint4(w[0], w[1], w[2], w[3]);
+    const uint32_t a = tile + wbase[q];
+    if (r & 1) asm volatile("ds_write_b128 %0, %1 offset:128" ::"v"(a), "v"(w) : "memory");
+    else asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(w) : "memory");
   }
 };
 
@@ -167,7 +183,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   // (KC,KC) products keep their operand tiles in a ring of five 32 KB slots (A and B tiles of
   // successive K tiles in turn) instead of two 64 KB stages: see the main loop.
   constexpr bool RING = (LA == OP_KC && LB == OP_KC);
-  constexpr int SMEM_BYTES = RING ? 5 * TILE_BYTES : 2 * STAGE_BYTES;
+  // products with exactly one register-staged operand use the same five slots: see their main loop
+  constexpr bool RING_MC = ((LA == OP_KC) != (LB == OP_KC));
+  constexpr int SMEM_BYTES = (RING || RING_MC) ? 5 * TILE_BYTES : 2 * STAGE_BYTES;
   __shared__ __attribute__((aligned(16))) char smem[SMEM_BYTES];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -270,14 +288,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   auto commit_regs = [&](int q, char* next_stage) {
     if (LA == OP_KC && LB == OP_MC) {
       if (q == 0) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-      mb.commit(q, next_stage + TILE_BYTES, tid);
+      mb.commit(q, lds_addr(next_stage + TILE_BYTES));
     } else if (LA == OP_MC && LB == OP_KC) {
       if (q == 0) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-      ma.commit(q, next_stage, tid);
+      ma.commit(q, lds_addr(next_stage));
     } else if (LA == OP_MC && LB == OP_MC) {
       if (q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      ma.commit(q, next_stage, tid);
-      mb.commit(q, next_stage + TILE_BYTES, tid);
+      ma.commit(q, lds_addr(next_stage));
+      mb.commit(q, lds_addr(next_stage + TILE_BYTES));
     }
   };
   // A second operand pair (A2, B2, K2; both K-contiguous, same leading dimensions) continues the
@@ -322,7 +340,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   };
   const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
   bf16x8_t xa[4], xb[4], ya[4], yb[4];
-  if constexpr (!RING) {
+  if constexpr (!RING && !RING_MC) {
   // ---- prologue: tile 0 into stage 0 -------------------------------------------------
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
@@ -332,8 +350,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
-    if (LA == OP_MC) ma.commit(q, smem, tid);
-    if (LB == OP_MC) mb.commit(q, smem + TILE_BYTES, tid);
+    if (LA == OP_MC) ma.commit(q, lds_addr(smem));
+    if (LB == OP_MC) mb.commit(q, lds_addr(smem + TILE_BYTES));
   }
   advance();
   __syncthreads();
@@ -387,6 +405,114 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     iteration(1);
   }
   if (nk & 1) iteration(0);
+  } else if constexpr (RING_MC) {
+  // ---- one direct and one register-staged operand: five 32 KB slots ---------------------------
+  // The register-staged operand's K tile t lives in slot t & 1, the direct operand's in slot
+  // 2 + t % 3.  While K tile t is multiplied: the staged loads of tile t+2 are requested during
+  // its first k-step (into the register set that tile t's own data left), the direct loads of
+  // tile t+2 during the next two k-steps (into the slot tile t-1 left), and in the last k-step
+  // before the barrier the registers holding tile t+1 are transposed into LDS.  Every request has
+  // more than a whole K tile's time before it is waited for, and two tiles' requests stay in
+  // flight across the barrier.
+  constexpr bool A_DIRECT = (LA == OP_KC);
+  LoaderKC& kd = *(A_DIRECT ? &ka : &kb_);
+  LoaderMC& mr = *(A_DIRECT ? &mb : &ma);
+  const int wr = A_DIRECT ? wn : wm, wd = A_DIRECT ? wm : wn;
+  uint32_t rr_addr[4], rd_addr[2][4];   // staged: slot 1 is an immediate away; direct: [slot pair][k-step]
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ (frow >> 1)) & 7) << 4);
+    rr_addr[ks] = (uint32_t)((wr * 128 + frow) * 128) + sw;
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) rd_addr[pr][ks] = (uint32_t)((2 + 2 * pr) * TILE_BYTES + (wd * 128 + frow) * 128) + sw;
+  }
+  // fragment q of k-step ks of a K tile with index t6 modulo 6
+  auto rfrag_mc = [&](int t6, int ks, int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
+    constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
+    constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
+    const int sr = t6 & 1, sd = t6 % 3;
+    const bool direct = (isA[q] != 0) == A_DIRECT;
+    const char* src = direct ? smem + rd_addr[sd >> 1][ks] + (sd & 1) * TILE_BYTES + idx[q] * 4096
+                             : smem + rr_addr[ks] + sr * TILE_BYTES + idx[q] * 4096;
+    if (isA[q]) fa[idx[q]] = *reinterpret_cast<const bf16x8_t*>(src);
+    else fb[idx[q]] = *reinterpret_cast<const bf16x8_t*>(src);
+  };
+  // prologue: staged 0, direct 0, staged 1, direct 1 requested; tile 0 made ready; staged 2 requested
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) mr.issue(q, h);
+    mr.next_tile();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) kd.issue(q, smem + (2 + h) * TILE_BYTES, wave);
+    kd.next_tile();
+  }
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+#pragma unroll
+  for (int q = 0; q < 8; ++q) mr.commit(q, lds_addr(smem), 0);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    rfrag_mc(0, 0, q, xa, xb);
+    mr.issue(q, 0);
+  }
+  mr.next_tile();
+  auto mc_iteration = [&](const int t6) __attribute__((always_inline)) {
+    const int nsr = (t6 & 1) ^ 1;                    // slot and register set of the staged tile t+1
+    char* d2 = smem + (2 + (t6 + 2) % 3) * TILE_BYTES;   // receives the direct tile t+2
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_mc(t6, 1, q, ya, yb);
+      if (q < 4) kd.issue(q, d2, wave);
+      mma2(q, xa, xb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_mc(t6, 2, q, xa, xb);
+      if (q < 4) kd.issue(4 + q, d2, wave);
+      mma2(q, ya, yb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    kd.next_tile();
+    // pending, oldest first: staged t+1, direct t+1, staged t+2, direct t+2 (8 loads each)
+    asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_mc(t6, 3, q, ya, yb);
+      mr.commit(q, lds_addr(smem + nsr * TILE_BYTES), nsr);
+      mma2(q, xa, xb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // tile t+1 complete in LDS for every wavefront, and nobody reads tile t's slots any more
+    asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      rfrag_mc((t6 + 1) % 6, 0, q, xa, xb);
+      mr.issue(q, nsr);
+      mma2(q, ya, yb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mr.next_tile();
+  };
+  int kt = 0;
+  for (; kt + 6 <= nk; kt += 6) {
+    mc_iteration(0);
+    mc_iteration(1);
+    mc_iteration(2);
+    mc_iteration(3);
+    mc_iteration(4);
+    mc_iteration(5);
+  }
+  if (kt < nk) mc_iteration(0);
+  if (kt + 1 < nk) mc_iteration(1);
+  if (kt + 2 < nk) mc_iteration(2);
+  if (kt + 3 < nk) mc_iteration(3);
+  if (kt + 4 < nk) mc_iteration(4);
   } else {
   // ---- (KC,KC): ring of five 32 KB slots ------------------------------------------------------
   // Operand tiles alternate through the slots: A of K tile t in slot 2t mod 5, B in slot 2t+1 mod 5.
