@@ -322,6 +322,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   // The touching loads return asynchronously into their destination registers, so these stay
   // reserved (never reused by the compiler) until the wait that follows the main loop.
   constexpr bool TOUCH = (EPI == EPI_GATE);
+  // Token ids of this wavefront's 128 output rows, lane l holding rows l and 64 + l, fetched here so
+  // that their latency passes under the main loop.  The epilogue takes each row's id from these
+  // registers by a lane permute: loading ids there would put a wait for the newest loads in front of
+  // every block of table-row requests, and with it a wait for all the stores issued before them
+  // (loads and stores return through one in-order counter), 3 to 4 us per block.
+  constexpr bool NEED_IDS = (EPI == EPI_GATE || EPI == EPI_DH || EPI == EPI_GATE_UPE || EPI == EPI_DH_UPE);
+  int row_id[2] = {0, 0};
+  if (NEED_IDS) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int m = m0 + wm * 128 + h * 64 + lane;
+      int id = p.ids[m < p.M ? m : p.M - 1];
+      if ((unsigned)id >= (unsigned)p.E_rows) {   // reported to the host, clamped so no access leaves the table
+        *p.flag = 1;
+        id = id < 0 ? 0 : p.E_rows - 1;
+      }
+      row_id[h] = id;
+    }
+  }
   uint32_t touched[4] = {0, 0, 0, 0};
   auto touch_epilogue_inputs = [&]() {
     if (!TOUCH) return;
@@ -329,10 +348,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     const int col = ncol < p.N ? ncol : 0;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int m = m0 + wm * 128 + h * 64 + lane;
-      const int mc = m < p.M ? m : p.M - 1;
-      int id = p.ids[mc];
-      if ((unsigned)id >= (unsigned)p.E_rows) id = id < 0 ? 0 : p.E_rows - 1;  // reported by the epilogue
+      const int id = row_id[h];
       const bf16_t* e = p.E + (size_t)id * p.N + col;
       asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
                    : "=&v"(touched[2 * h]), "=&v"(touched[2 * h + 1]) : "v"(e) : "memory");
@@ -646,11 +662,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       const int m = m0 + wm * 128 + i * 32 + pass * 4 + srow;
       const int mc = m < p.M ? m : p.M - 1;
       if (USE_E) {
-        int id = p.ids[mc];
-        if ((unsigned)id >= (unsigned)p.E_rows) {
-          *p.flag = 1;
-          id = id < 0 ? 0 : p.E_rows - 1;
-        }
+        const int r = i * 32 + pass * 4 + srow;   // row within the wavefront's 128: held by lane r & 63
+        const int id = __builtin_amdgcn_ds_bpermute((r & 63) * 4, row_id[i >> 1]);
         ev[buf][pass] = *reinterpret_cast<const uint4*>(p.E + (size_t)id * p.N + n_ld);
       }
       if (USE_UP) uv[buf][pass] = *reinterpret_cast<const uint4*>(p.inUp + (size_t)mc * p.N + n_ld);
