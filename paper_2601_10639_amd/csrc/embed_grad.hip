@@ -419,7 +419,10 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(const void* __restrict_
     store_cols<COLS>(dst, acc);
   };
 
-  constexpr int UNR = 16;
+  // all of the chunk's row loads are requested before the first store: loads and stores return
+  // through one in-order counter, so a load requested after a store is not seen before that store
+  // has been acknowledged
+  constexpr int UNR = SEG_ROWS;
 #pragma unroll
   for (int kb = 0; kb < SEG_ROWS; kb += UNR) {
     typename RowVec<BF16>::raw_t data[UNR];
