@@ -218,6 +218,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     tile_of_block(blockIdx.x, gridDim.x, ntm, ntn, tm, tn);
   }
   const int m0 = tm * BM, n0 = tn * BN;
+  // K rotation.  Workgroups on XCD x start their K loop x eighths of the way in and wrap around, so
+  // the eight XCDs stream eight different stretches of the operands' rows at any moment instead of
+  // the same one (measured: the down product, whose two operands have the same 16 KB row pitch, ran
+  // 8 % slower without it; the other products with two direct operands are unchanged, and the
+  // weight-gradient products gained nothing from the same rotation, so they do not rotate).  The sum over k is the same set of products in
+  // a rotated order.  `rot` is the first K element of this workgroup's loop; 0 = no rotation.
+  int rot = 0;
+  if (RING && !p.A2) {
+    const int nk_all = (p.K + BK - 1) / BK;
+    if (nk_all >= 16) rot = (int)((long)(blockIdx.x & 7) * nk_all / 8) * BK;
+  }
+  if (RING && rot > 0) {   // expressed as two operand pairs: [rot, K) of A, B and then [0, rot)
+    p.A2 = p.A; p.B2 = p.B; p.K2 = rot;
+    p.A += rot; p.B += rot; p.K -= rot; p.kc_skip += rot;
+  }
 
   f32x16_t acc[4][4];
 #pragma unroll
@@ -558,10 +573,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   };
   int a_to_switch = p.A2 ? nk1 : -1, b_to_switch = a_to_switch;
   auto next_A = [&]() {
-    if (--a_to_switch == 0) ka.win.set(p.A2, (int64_t)p.M * p.lda * 2); else ka.next_tile();
+    if (--a_to_switch == 0) ka.win.set(p.A2, ((int64_t)p.M * p.lda - (p.kc_skip - rot)) * 2); else ka.next_tile();
   };
   auto next_B = [&]() {
-    if (--b_to_switch == 0) kb_.win.set(p.B2, (int64_t)p.N * p.ldb * 2); else kb_.next_tile();
+    if (--b_to_switch == 0) kb_.win.set(p.B2, ((int64_t)p.N * p.ldb - (p.kc_skip - rot)) * 2); else kb_.next_tile();
   };
   // prologue: A0, B0, A1, B1 into slots 0..3
 #pragma unroll
