@@ -84,6 +84,23 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p) {
   const int kt0 = z * per;
   const int nk = (nk_all - kt0) < per ? (nk_all - kt0) : per;   // may be <= 0: an all-zero partial
 
+  // ---- gate epilogue inputs, requested up front -------------------------------------------------
+  // The epilogue multiplies by one gathered table row per output row.  Token ids are requested
+  // first of all and the table rows right after the first operand tiles, so both latencies pass
+  // under the main loop instead of standing, one after the other, at the end of a 20 us kernel.
+  // thread -> rows it * 32 + (tid >> 4), it = 0..3, columns (tid & 15) * 4 .. +3 of the tile
+  const int c4 = tid & 15;
+  const int n = n0 + c4 * 4;
+  int ids4[4] = {0, 0, 0, 0};
+  uint2 ev[4];
+  if (EPI == EPI_GATE) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int m = m0 + it * 32 + (tid >> 4);
+      ids4[it] = p.ids[m < p.M ? m : p.M - 1];
+    }
+  }
+
   // ---- operand loads: wavefront w brings A row blocks 2w, 2w+1 and B row block w of a tile ------
   // lane -> row (lane >> 3) of the 8-row block, 16-byte chunk (lane & 7) of the 128-byte row
   const rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(p.A), 0, p.M * p.lda * 2, 0x00020000);
@@ -142,6 +159,18 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p) {
   // tile t run.  Requests past the K range read other (valid or zero) bytes that are never used.
 #pragma unroll
   for (int s = 0; s < DEPTH; ++s) request(ring[s]);
+  if (EPI == EPI_GATE) {
+    const int n_ld = n < p.N ? n : 0;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      int id = ids4[it];
+      if ((unsigned)id >= (unsigned)p.E_rows) {   // reported to the host, clamped so no access leaves the table
+        *p.flag = 1;
+        id = id < 0 ? 0 : p.E_rows - 1;
+      }
+      ev[it] = *reinterpret_cast<const uint2*>(p.E + (size_t)id * p.N + n_ld);
+    }
+  }
   commit(ring[0], 0);
   request(ring[0]);
   __syncthreads();
@@ -190,25 +219,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p) {
   __syncthreads();
 
   // ---- sum of the quarters and epilogue: thread -> row (idx >> 4), columns (idx & 15) * 4 .. +3 ----
-  const int c4 = tid & 15;
-  const int n = n0 + c4 * 4;
   if (n >= p.N) return;
-  int ids4[4];
-  uint2 ev[4];
-  if (EPI == EPI_GATE) {
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int m = m0 + it * 32 + (tid >> 4);
-      int id = p.ids[m < p.M ? m : p.M - 1];
-      if ((unsigned)id >= (unsigned)p.E_rows) {
-        *p.flag = 1;
-        id = id < 0 ? 0 : p.E_rows - 1;
-      }
-      ids4[it] = id;
-    }
-#pragma unroll
-    for (int it = 0; it < 4; ++it) ev[it] = *reinterpret_cast<const uint2*>(p.E + (size_t)ids4[it] * p.N + n);
-  }
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int row = it * 32 + (tid >> 4);
