@@ -90,10 +90,13 @@ def test_fp32_ragged_token_counts(T):
     _pipeline_case(s, T, seed=2)
 
 
-@pytest.mark.parametrize("T,d,F", [(600, 192, 576), (257, 64, 64), (1, 128, 320), (1100, 512, 256), (2100, 128, 320)])
+@pytest.mark.parametrize("T,d,F", [(600, 192, 576), (257, 64, 64), (1, 128, 320), (1100, 512, 256), (2100, 128, 320),
+                                   (600, 1088, 1152)])
 def test_bf16_several_tiles_and_ragged_tails(T, d, F):
     # 256-wide tiles: these sizes give full tiles plus a ragged last tile in every dimension; the
-    # weight-gradient products of the last two are cut along K (2 slices; 4 slices of 9, 9, 9, 6 K tiles)
+    # weight-gradient products of the 4th and 5th are cut along K (2 slices; 4 slices of 9, 9, 9, 6 K tiles);
+    # the last has 17 and 18 K tiles in its forward and activation-gradient products, enough for the
+    # workgroups to start their K loops at different K tiles (rotation per XCD) and wrap around
     s = inputs.StemShape("bf16-ragged", d, F, 1000, 1, T, "bf16")
     _pipeline_case(s, T, seed=3)
 
