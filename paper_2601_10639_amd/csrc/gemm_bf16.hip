@@ -47,7 +47,6 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = 256 * BK * 2;  // one operand tile in LDS
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;
 constexpr uint32_t OOB = 0x80000000u;  // a buffer offset beyond any operand: reads as zero
 
 __device__ __forceinline__ uint32_t lds_addr(const char* p) {   // p points into LDS
@@ -188,8 +187,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   constexpr bool RING = (LA == OP_KC && LB == OP_KC);
   // products with exactly one register-staged operand use the same five slots: see their main loop
   constexpr bool RING_MC = ((LA == OP_KC) != (LB == OP_KC));
-  constexpr int SMEM_BYTES = (RING || RING_MC) ? 5 * TILE_BYTES : 2 * STAGE_BYTES;
-  __shared__ __attribute__((aligned(16))) char smem[SMEM_BYTES];
+  static_assert(RING || RING_MC, "at least one operand takes the direct path");
+  __shared__ __attribute__((aligned(16))) char smem[5 * TILE_BYTES];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -250,25 +249,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane, p.kc_skip); else ma.init(p.A, p.lda, p.M, p.K_mc > 0 ? p.K_mc : p.K, m0, tid);
   if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane, p.kc_skip); else mb.init(p.B, p.ldb, p.N, p.K_mc > 0 ? p.K_mc : p.K, n0, tid);
 
-  // fragment addresses: per k-step one register per operand and stage, rows via immediates
+  // fragments: lane -> row (lane & 31) of a 32-row block, k half (lane >> 5) of a k-step; within a k-step
+  // they are read in the order a0,b0,b1,a1,b2,b3,a2,a3
   const int frow = lane & 31, fk = lane >> 5;
-  uint32_t fa_addr[2][4], fb_addr[2][4];
-#pragma unroll
-  for (int s = 0; s < 2; ++s)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ (frow >> 1)) & 7) << 4);
-      fa_addr[s][ks] = (uint32_t)(s * STAGE_BYTES + (wm * 128 + frow) * 128) + sw;
-      fb_addr[s][ks] = (uint32_t)(s * STAGE_BYTES + TILE_BYTES + (wn * 128 + frow) * 128) + sw;
-    }
-
-  // fragment q (0..7) of a k-step, in load order a0,b0,b1,a1,b2,b3,a2,a3
-  auto rfrag1 = [&](int stage, int ks, int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
-    constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
-    constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
-    if (isA[q]) fa[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + fa_addr[stage][ks] + idx[q] * 4096);
-    else fb[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + fb_addr[stage][ks] + idx[q] * 4096);
-  };
   // MFMA pair q (0..7), in an order that consumes fragments in the order they were read
   auto mma2 = [&](int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
     constexpr int ii[16] = {0, 0, 1, 1, 0, 1, 0, 1, 2, 2, 2, 2, 3, 3, 3, 3};
@@ -280,56 +263,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     }
   };
 
-  // Loads of the next tile, by slot: `phase` 3 = after the barrier (last k-step of the
-  // previous iteration), 0..2 = k-steps of this iteration; q = position within the k-step.
-  // Register-staged (MC) operands are fetched first so their data can be transposed and
-  // written to LDS in k-step 2, while direct-to-LDS loads may still be in flight.
-  auto issue_loads = [&](int phase, int q, char* next_stage) {
-    if (LA == OP_KC && LB == OP_KC) {        // 16 direct loads: 8 in phase 3, 4 + 4 in phases 0, 1
-      int n = -1;
-      if (phase == 3) n = q; else if (phase == 0 && q < 4) n = 8 + q; else if (phase == 1 && q < 4) n = 12 + q;
-      if (n >= 0) { if (n & 1) kb_.issue(n >> 1, next_stage + TILE_BYTES, wave); else ka.issue(n >> 1, next_stage, wave); }
-    } else if (LA == OP_KC && LB == OP_MC) {  // B through registers in phase 3, A direct in phases 0, 1
-      if (phase == 3) mb.issue(q);
-      else if (phase == 0 && q < 4) ka.issue(q, next_stage, wave);
-      else if (phase == 1 && q < 4) ka.issue(4 + q, next_stage, wave);
-    } else if (LA == OP_MC && LB == OP_KC) {  // A through registers in phase 3, B direct in phases 0, 1
-      if (phase == 3) ma.issue(q);
-      else if (phase == 0 && q < 4) kb_.issue(q, next_stage + TILE_BYTES, wave);
-      else if (phase == 1 && q < 4) kb_.issue(4 + q, next_stage + TILE_BYTES, wave);
-    } else {                                  // both through registers: A in phase 3, B in phase 0
-      if (phase == 3) ma.issue(q);
-      else if (phase == 0) mb.issue(q);
-    }
-  };
-  // Register-staged operands go to LDS during k-step 2 (their loads were the oldest issued).
-  auto commit_regs = [&](int q, char* next_stage) {
-    if (LA == OP_KC && LB == OP_MC) {
-      if (q == 0) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-      mb.commit(q, lds_addr(next_stage + TILE_BYTES));
-    } else if (LA == OP_MC && LB == OP_KC) {
-      if (q == 0) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-      ma.commit(q, lds_addr(next_stage));
-    } else if (LA == OP_MC && LB == OP_MC) {
-      if (q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      ma.commit(q, lds_addr(next_stage));
-      mb.commit(q, lds_addr(next_stage + TILE_BYTES));
-    }
-  };
   // A second operand pair (A2, B2, K2; both K-contiguous, same leading dimensions) continues the
   // sum: after the K tiles of the first pair the windows move to the second.
   const int nk1 = (p.K + BK - 1) / BK;
-  int tiles_to_switch = (LA == OP_KC && LB == OP_KC && p.A2) ? nk1 : -1;
-  auto advance = [&]() {
-    if (LA == OP_KC && LB == OP_KC && --tiles_to_switch == 0) {
-      ka.win.set(p.A2, (int64_t)p.M * p.lda * 2);
-      kb_.win.set(p.B2, (int64_t)p.N * p.ldb * 2);
-      return;
-    }
-    if (LA == OP_KC) ka.next_tile(); else ma.next_tile();
-    if (LB == OP_KC) kb_.next_tile(); else mb.next_tile();
-  };
-
   const int nk = nk1 + ((LA == OP_KC && LB == OP_KC && p.A2) ? (p.K2 + BK - 1) / BK : 0);
   // The gate epilogue reads one gathered table row per output row.  A few K tiles before the end
   // of the main loop each lane touches the 128-byte lines its wavefront will need, so that they
@@ -374,72 +310,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   };
   const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
   bf16x8_t xa[4], xb[4], ya[4], yb[4];
-  if constexpr (!RING && !RING_MC) {
-  // ---- prologue: tile 0 into stage 0 -------------------------------------------------
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    if (LA == OP_KC) ka.issue(q, smem, wave); else ma.issue(q);
-    if (LB == OP_KC) kb_.issue(q, smem + TILE_BYTES, wave); else mb.issue(q);
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    if (LA == OP_MC) ma.commit(q, lds_addr(smem));
-    if (LB == OP_MC) mb.commit(q, lds_addr(smem + TILE_BYTES));
-  }
-  advance();
-  __syncthreads();
-#pragma unroll
-  for (int q = 0; q < 8; ++q) rfrag1(0, 0, q, xa, xb);
-#pragma unroll
-  for (int q = 0; q < 8; ++q) issue_loads(3, q, smem + STAGE_BYTES);
-
-  // ---- main loop, two K tiles per trip (stage 0 then stage 1) --------------------------
-  auto iteration = [&](const int st) __attribute__((always_inline)) {
-    char* next_stage = smem + (st ^ 1) * STAGE_BYTES;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag1(st, 1, q, ya, yb);
-      issue_loads(0, q, next_stage);
-      mma2(q, xa, xb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag1(st, 2, q, xa, xb);
-      issue_loads(1, q, next_stage);
-      mma2(q, ya, yb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag1(st, 3, q, ya, yb);
-      commit_regs(q, next_stage);
-      mma2(q, xa, xb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // next tile complete in LDS for every wavefront, and nobody still reads the stage
-    // that the loads after this barrier overwrite
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    advance();
-    char* after_next = smem + st * STAGE_BYTES;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag1(st ^ 1, 0, q, xa, xb);
-      issue_loads(3, q, after_next);
-      mma2(q, ya, yb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  for (int kt = 0; kt + 1 < nk; kt += 2) {
-    if (TOUCH && kt == touch_at) touch_epilogue_inputs();
-    iteration(0);
-    iteration(1);
-  }
-  if (nk & 1) iteration(0);
-  } else if constexpr (RING_MC) {
+  if constexpr (RING_MC) {
   // ---- one direct and one register-staged operand: five 32 KB slots ---------------------------
   // The register-staged operand's K tile t lives in slot t & 1, the direct operand's in slot
   // 2 + t % 3.  While K tile t is multiplied: the staged loads of tile t+2 are requested during
@@ -751,9 +622,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
           unpack8(gv[i & 1][pass], gz);
 #pragma unroll
           for (int q = 0; q < 8; ++q) {
+            // dU = C SiLU(G) = C g s;  dG = C e SiLU'(G) = C e s (1 + g (1 - s)) = e (dU (1 - s) + C s)
             const float sg = sigmoidf_fast(gz[q]);
-            du[q] = c[q] * gz[q] * sg;
-            dg[q] = c[q] * e[q] * sg * (1.0f + gz[q] * (1.0f - sg));
+            const float cs = c[q] * sg;
+            du[q] = cs * gz[q];
+            dg[q] = e[q] * fmaf(du[q], 1.0f - sg, cs);
           }
           if (ok) {
             *reinterpret_cast<uint4*>(p.outdU + o) = pack8(du);
@@ -819,14 +692,10 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
     if (epi == EPI_GATE_UPE) return launch<OP_KC, OP_KC, EPI_GATE_UPE>(ctx, kid, a, s);
     if (epi == EPI_DH_UP) return launch<OP_KC, OP_KC, EPI_DH_UP>(ctx, kid, a, s);
     if (epi == EPI_DH_UPE) return launch<OP_KC, OP_KC, EPI_DH_UPE>(ctx, kid, a, s);
-  } else if (la == OP_KC && lb == OP_MC) {
-    if (epi == EPI_BF16) return launch<OP_KC, OP_MC, EPI_BF16>(ctx, kid, a, s);
-    if (epi == EPI_DH) return launch<OP_KC, OP_MC, EPI_DH>(ctx, kid, a, s);
+  } else if (la == OP_KC && lb == OP_MC) {   // weight gradients: one operand rows-contiguous
     if (epi == EPI_F32) return launch<OP_KC, OP_MC, EPI_F32>(ctx, kid, a, s);
   } else if (la == OP_MC && lb == OP_KC) {
     if (epi == EPI_F32) return launch<OP_MC, OP_KC, EPI_F32>(ctx, kid, a, s);
-  } else if (la == OP_MC && lb == OP_MC) {
-    if (epi == EPI_F32) return launch<OP_MC, OP_MC, EPI_F32>(ctx, kid, a, s);
   }
   return hipErrorInvalidValue;
 }
