@@ -289,8 +289,8 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
   const int d = c->desc.d_model, F = c->desc.d_ff;
   if (T == 0) {
     if (!accumulate) {
-      HIP_TRY(c, hipMemsetAsync(dW_gate, 0, (size_t)F * d * 4, s));
-      HIP_TRY(c, hipMemsetAsync(dW_down, 0, (size_t)F * d * 4, s));
+      HIP_TRY(c, stem_fill_zero(dW_gate, (size_t)F * d * 4, s));
+      HIP_TRY(c, stem_fill_zero(dW_down, (size_t)F * d * 4, s));
     }
     return STEM_OK;
   }
@@ -434,9 +434,9 @@ stem_status stem_ffn_up_backward(stem_ctx* c, const void* dy, const void* x, con
   const int d = c->desc.d_model, F = c->desc.d_ff;
   if (T == 0) {
     if (!accumulate) {
-      HIP_TRY(c, hipMemsetAsync(dW_gate, 0, (size_t)F * d * 4, s));
-      HIP_TRY(c, hipMemsetAsync(dW_up, 0, (size_t)F * d * 4, s));
-      HIP_TRY(c, hipMemsetAsync(dW_down, 0, (size_t)F * d * 4, s));
+      HIP_TRY(c, stem_fill_zero(dW_gate, (size_t)F * d * 4, s));
+      HIP_TRY(c, stem_fill_zero(dW_up, (size_t)F * d * 4, s));
+      HIP_TRY(c, stem_fill_zero(dW_down, (size_t)F * d * 4, s));
     }
     return STEM_OK;
   }
@@ -509,8 +509,8 @@ stem_status stem_embed_grad(stem_ctx* c, const int32_t* ids, const void* dU, int
   if (!seg_offsets || !n_uniq) return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: null seg_offsets / n_uniq");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (T == 0) {
-    HIP_TRY(c, hipMemsetAsync(n_uniq, 0, 4, s));
-    HIP_TRY(c, hipMemsetAsync(seg_offsets, 0, 4, s));
+    HIP_TRY(c, stem_fill_zero(n_uniq, 4, s));
+    HIP_TRY(c, stem_fill_zero(seg_offsets, 4, s));
     return STEM_OK;
   }
   if (!ids || !sorted_ids || !perm || !uniq_ids)

@@ -171,6 +171,19 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
 
 }  // namespace
 
+// Zero fill by a kernel rather than hipMemsetAsync, so that every call of the library can be recorded
+// into a HIP graph (memset nodes have replayed wrongly on this platform).
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t words) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+hipError_t stem_fill_zero(void* p, size_t bytes, hipStream_t s) {   // bytes is a multiple of 4
+  if (bytes == 0) return hipSuccess;
+  const size_t words = bytes / 4;
+  const unsigned grid = (unsigned)std::min<size_t>((words + 255) / 256, 2048);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, static_cast<uint32_t*>(p), words);
+  return hipGetLastError();
+}
+
 hipError_t stem_transpose_bf16(stem_ctx* ctx, const void* in, int R, int C, void* out, int ldo, hipStream_t s) {
   if (R <= 0 || C <= 0) return hipSuccess;
   ProfScope ps(ctx, K_TRANSPOSE, s);

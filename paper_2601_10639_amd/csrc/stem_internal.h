@@ -179,6 +179,7 @@ hipError_t stem_sgemm(stem_ctx* ctx, int kid, const float* A, int64_t sam, int64
                       int64_t sbn, int64_t sbk, float* C, int M, int N, int K, int accumulate, hipStream_t s);
 // out[c,r] = in[r,c] (bf16), leading dimension ldo, zero padding beyond R
 hipError_t stem_transpose_bf16(stem_ctx* ctx, const void* in, int R, int C, void* out, int ldo, hipStream_t s);
+hipError_t stem_fill_zero(void* p, size_t bytes, hipStream_t s);   // a kernel, not a memset node
 // H = SiLU(G) * E[ids]; is_bf16 selects the element type of G, E, H
 hipError_t stem_silu_gather(stem_ctx* ctx, int is_bf16, const void* G, const int32_t* ids, const void* E,
                             int E_rows, void* H, int64_t T, int F, hipStream_t s);
