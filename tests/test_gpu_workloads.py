@@ -219,6 +219,73 @@ def _prefetch_case(shape, T, ids_np, seed, mode=None):
     return x, Wg, Wd, E_host, y, n
 
 
+def test_training_step_can_be_captured_in_a_hip_graph():
+    """Forward, backward, table gradient and sparse AdamW of one layer captured once and replayed three
+    times (the optimiser state moves on with every replay), with eager work and synchronisations
+    between the replays; every replay must equal the same sequence run eagerly, bit for bit."""
+    shape = inputs.StemShape("train-graph", 256, 1024, 3000, 1, 1100, "bf16")
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    inp = inputs.layer_inputs(shape, seed=41, device=DEV)
+    ctx = Hn.make_ctx(shape, T)
+    bf = torch.bfloat16
+    y = torch.empty(T, d, dtype=bf, device=DEV)
+    G = torch.empty(T, F, dtype=bf, device=DEV)
+    H = torch.empty_like(G)
+    dU = torch.empty_like(G)
+    dx = torch.empty_like(y)
+    dWg = torch.empty(F, d, device=DEV)
+    dWd = torch.empty(d, F, device=DEV)
+    cap = min(T, V)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    sorted_ids, perm = torch.empty(T, **i32), torch.empty(T, **i32)
+    uniq, offs, n_uniq = torch.empty(cap, **i32), torch.empty(cap + 1, **i32), torch.zeros(1, **i32)
+    rows = torch.empty(cap, F, device=DEV)
+    E = inp["E"].clone()
+    master, m, v = E.float(), torch.zeros(V, F, device=DEV), torch.zeros(V, F, device=DEV)
+
+    def reset():
+        E.copy_(inp["E"])
+        master.copy_(inp["E"].float())
+        m.zero_()
+        v.zero_()
+
+    def step():
+        L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, y, G, H)
+        L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, H, dx, dWg, dWd, dU)
+        L.stem_embed_grad(ctx, inp["ids"], dU, sorted_ids, perm, uniq, offs, n_uniq, rows)
+        L.stem_embed_sparse_adamw(ctx, uniq, n_uniq, rows, E, master, m, v, step=1, **Hn.ADAMW)
+
+    watched = (y, dx, dWg, dWd, E, master, m, v)
+    reset()
+    want = []
+    for r in range(3):
+        step()
+        torch.cuda.synchronize()
+        want.append([t.clone() for t in watched])
+    assert not torch.equal(want[0][4], want[2][4])      # the table does move from step to step
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                        # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    reset()
+    for r in range(3):
+        y.fill_(3.0)                  # eager work between replays
+        dWg.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, exp in zip(watched, want[r]):
+            assert torch.equal(got, exp), r
+    L.stem_sync_status(ctx)
+    ctx.close()
+
+
 @pytest.mark.parametrize("dtype,mode", [("bf16", None), ("bf16", "memcpy"), ("f32", None)])
 def test_prefetch_rows_small(dtype, mode):
     shape = inputs.StemShape("host-small", 128, 256, 5000, 1, 3000, dtype)
