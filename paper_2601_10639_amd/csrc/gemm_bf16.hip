@@ -15,9 +15,11 @@
 // out-of-range rows / k read as zero, so ragged edges need no branches.
 //
 // LDS tile layout: row r (an m or n index within the tile) owns 128 bytes = 8 chunks of
-// 8 bf16; chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7).  With that XOR a
-// ds_read_b128 of one chunk column over 16 consecutive rows touches all 64 banks once
-// (SQ_LDS_BANK_CONFLICT reads 0 for this kernel).
+// 8 bf16; chunk c of row r sits at chunk slot c ^ ((r >> 1) ^ ((r >> 3) & 3)) & 7.  With the
+// first term a ds_read_b128 of one chunk column over 16 consecutive rows touches all 64 banks
+// once (SQ_LDS_BANK_CONFLICT reads 0 for the products with two direct operands); the second term
+// spreads rows 8 and 16 apart, which the transposing stores of a register-staged operand write
+// together (2-way instead of 4-way conflicts there).
 //
 // Schedule.  One iteration = one K tile = 4 k-steps of 16 MFMAs.  Fragments are double
 // buffered in registers: while the MFMAs of k-step s run, the 8 fragment reads of step
@@ -52,8 +54,11 @@ constexpr uint32_t OOB = 0x80000000u;  // a buffer offset beyond any operand: re
 __device__ __forceinline__ uint32_t lds_addr(const char* p) {   // p points into LDS
   return (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<char*>(p);
 }
+// chunk slot swizzle of a tile row (only bits 1..4 of the row: the same for rows 32 apart, so the
+// fragments of a wavefront's four 32-row blocks sit at one address plus immediates)
+__device__ __forceinline__ int lds_swz(int row) { return ((row >> 1) ^ ((row >> 3) & 3)) & 7; }
 __device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
-  return (uint32_t)(row * 128 + (((chunk ^ (row >> 1)) & 7) << 4));
+  return (uint32_t)(row * 128 + (((chunk ^ lds_swz(row)) & 7) << 4));
 }
 
 // A buffer resource that moves along the operand: base advances, the record count shrinks.
@@ -86,7 +91,7 @@ struct LoaderKC {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = (wave * 8 + i) * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ ((row >> 1) & 7);
+      const int c = (lane & 7) ^ lds_swz(row);
       off[i] = (row0 + row) < rows ? (uint32_t)(((int64_t)(row0 + row) * ld + c * 8) * 2) : OOB;
     }
   }
@@ -326,7 +331,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   uint32_t rr_addr[4], rd_addr[2][4];   // staged: slot 1 is an immediate away; direct: [slot pair][k-step]
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ (frow >> 1)) & 7) << 4);
+    const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ lds_swz(frow)) & 7) << 4);
     rr_addr[ks] = (uint32_t)((wr * 128 + frow) * 128) + sw;
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) rd_addr[pr][ks] = (uint32_t)((2 + 2 * pr) * TILE_BYTES + (wd * 128 + frow) * 128) + sw;
@@ -433,7 +438,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   for (int pr = 0; pr < 3; ++pr)
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ (frow >> 1)) & 7) << 4);
+      const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ lds_swz(frow)) & 7) << 4);
       ra_addr[pr][ks] = (uint32_t)(pr * 2 * TILE_BYTES + (wm * 128 + frow) * 128) + sw;
       rb_addr[pr][ks] = (uint32_t)(pr * 2 * TILE_BYTES + (wn * 128 + frow) * 128) + sw;
     }
