@@ -15,11 +15,13 @@
 // out-of-range rows / k read as zero, so ragged edges need no branches.
 //
 // LDS tile layout: row r (an m or n index within the tile) owns 128 bytes = 8 chunks of
-// 8 bf16; chunk c of row r sits at chunk slot c ^ ((r >> 1) ^ ((r >> 3) & 3)) & 7.  With the
-// first term a ds_read_b128 of one chunk column over 16 consecutive rows touches all 64 banks
-// once (SQ_LDS_BANK_CONFLICT reads 0 for the products with two direct operands); the second term
-// spreads rows 8 and 16 apart, which the transposing stores of a register-staged operand write
-// together (2-way instead of 4-way conflicts there).
+// 8 bf16; chunk c of row r sits at chunk slot (c ^ (r >> 1) ^ (((r >> 3) & 3) << 1)) & 7.  With
+// the first term a ds_read_b128 of one chunk column over 16 consecutive rows touches all 64
+// banks once; the second term spreads rows 8 and 16 apart, which the transposing stores of a
+// register-staged operand write together.  Measured per instruction with four wavefronts
+// issuing: fragment reads 16 clocks (conflict-free) with or without the second term, those stores
+// 64 clocks with it and 128 without; XORing the same two row bits into slot bits 0 and 1 instead
+// makes the stores as cheap but the reads conflict 2-way.
 //
 // Schedule.  One iteration = one K tile = 4 k-steps of 16 MFMAs.  Fragments are double
 // buffered in registers: while the MFMAs of k-step s run, the 8 fragment reads of step
@@ -56,7 +58,7 @@ __device__ __forceinline__ uint32_t lds_addr(const char* p) {   // p points into
 }
 // chunk slot swizzle of a tile row (only bits 1..4 of the row: the same for rows 32 apart, so the
 // fragments of a wavefront's four 32-row blocks sit at one address plus immediates)
-__device__ __forceinline__ int lds_swz(int row) { return ((row >> 1) ^ ((row >> 3) & 3)) & 7; }
+__device__ __forceinline__ int lds_swz(int row) { return ((row >> 1) ^ (((row >> 3) & 3) << 1)) & 7; }
 __device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
   return (uint32_t)(row * 128 + (((chunk ^ lds_swz(row)) & 7) << 4));
 }
