@@ -178,6 +178,12 @@ def main() -> int:
     if os.path.exists(tpath):
         with open(tpath) as fh:
             traffic = {k: v for k, v in json.load(fh).items() if not k.startswith("_")}
+    # MFMA-busy fraction and sustained shader clock per kernel from hardware counters, same condition
+    counters = {}
+    cpath = os.path.join(ROOT, "profiles", "mfma_util_%s.json" % shape.name.replace("-", "_"))
+    if os.path.exists(cpath) and variant == "stem":
+        with open(cpath) as fh:
+            counters = {k: v for k, v in json.load(fh).items() if not k.startswith("_")}
     gemms = {k: v for k, v in kernels.items() if k.startswith("gemm_")}
     dom = max(gemms, key=lambda k: gemms[k]["avg_ms"] * gemms[k]["launches"])
     all_gemm_ms = sum(v["avg_ms"] for v in gemms.values())
@@ -190,6 +196,7 @@ def main() -> int:
         "unit": "TFLOP/s",
         "frac": round(gemms[dom]["tflops"] / peak_tf, 4),
         "traffic": traffic.get(dom),
+        "counters": counters.get(dom),
         "all_gemms_tflops": round(n_gemm_units * gemm_flop / (all_gemm_ms * 1e-3) / 1e12, 2),
         "all_gemms_frac": round(n_gemm_units * gemm_flop / (all_gemm_ms * 1e-3) / 1e12 / peak_tf, 4),
     }
