@@ -25,9 +25,10 @@
  *   - Errors: argument and shape errors are detected on the host before anything
  *     is launched and returned as a status; stem_last_error() gives the text.
  *     Token ids outside [0, E_rows) never cause an out-of-bounds access: kernels
- *     clamp them to a valid row and raise a sticky flag that the next libstem call
- *     on the context (or stem_sync_status) reports as STEM_ERR_ID_RANGE; results
- *     computed from such ids are unspecified.
+ *     clamp them to a valid row (a negative id to row 0, any other to the last row)
+ *     and raise a sticky flag that the next libstem call on the context (or
+ *     stem_sync_status) reports as STEM_ERR_ID_RANGE; the results of the tokens with
+ *     valid ids are unaffected.
  *   - The context owns only scratch memory (sort buffers, partial sums, the
  *     internal H and dG buffers, pinned staging, one side stream and its events),
  *     all sized by stem_create from max_tokens; no call allocates.

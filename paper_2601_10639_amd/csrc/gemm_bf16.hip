@@ -311,8 +311,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     for (int h = 0; h < 2; ++h) {
       const int id = row_id[h];
       const bf16_t* e = p.E + (size_t)id * p.N + col;
-      asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
-                   : "=&v"(touched[2 * h]), "=&v"(touched[2 * h + 1]) : "v"(e) : "memory");
+      // the second line of the row's 128 columns exists only if the matrix is that wide (d_ff may be
+      // 64 modulo 128): otherwise touch the first line twice rather than the next row's memory
+      const bf16_t* e2 = col + 64 < p.N ? e + 64 : e;
+      asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %3, off"
+                   : "=&v"(touched[2 * h]), "=&v"(touched[2 * h + 1]) : "v"(e), "v"(e2) : "memory");
     }
   };
   const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
@@ -566,6 +569,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       if (DH_LIKE) gv[buf][pass] = *reinterpret_cast<const uint4*>(p.inG + (size_t)mc * p.N + n_ld);
     }
   };
+  // Outputs leave through buffer stores: a lane outside the matrix (ragged last tile) is given an
+  // offset beyond the buffer and the hardware drops its store, so the element-wise part below is
+  // straight-line code that the compiler schedules as a whole (the staged values of all eight
+  // passes are read from LDS up front and the arithmetic of one pass covers the latency of the
+  // next; with a branch around every store each pass waited for its own LDS reads: stamps inside
+  // the kernel, 5.7 K clocks per 32-row block against 3.6 K of arithmetic).
+  auto out_rsrc = [&](void* ptr, int esize) {
+    return __builtin_amdgcn_make_buffer_rsrc(ptr, 0, ptr ? (int)((int64_t)p.M * p.N * esize) : 0, 0x00020000);
+  };
+  rsrc_t r0, r1;   // EPI_BF16 / EPI_F32: C;  gate-like: G (may be absent), H;  dH-like: dU, dG
+  if (EPI == EPI_BF16) r0 = r1 = out_rsrc(p.C, 2);
+  else if (EPI == EPI_F32) r0 = r1 = out_rsrc(p.C, 4);
+  else if (GATE_LIKE) { r0 = out_rsrc(p.outG, 2); r1 = out_rsrc(p.outH, 2); }
+  else { r0 = out_rsrc(p.outdU, 2); r1 = out_rsrc(p.outdG, 2); }
+  auto store16 = [&](rsrc_t r, uint32_t off, uint4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), r, off, 0, 0);
+  };
   prefetch(0, 0);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -583,29 +603,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    f32x4_t cv[8][2];
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int r = pass * 4 + srow;
+      cv[pass][0] = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4);
+      cv[pass][1] = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4 + 16);
+    }
 #pragma unroll
     for (int pass = 0; pass < 8; ++pass) {
       const int r = pass * 4 + srow;
       const int m = m0 + wm * 128 + i * 32 + r;
-      const f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4);
-      const f32x4_t c1 = *reinterpret_cast<const f32x4_t*>(stg + r * SROW + scol * 4 + 16);
+      const f32x4_t c0 = cv[pass][0], c1 = cv[pass][1];
       const float c[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
       const bool ok = n_ok && m < p.M;
-      const size_t o = (size_t)m * p.N + n;
+      const uint32_t o = ok ? (uint32_t)m * (uint32_t)p.N + (uint32_t)n : 0u;   // element index, < 2^30
+      const uint32_t o2 = ok ? o * 2u : OOB, o4 = ok ? o * 4u : OOB;
       if (EPI == EPI_BF16) {
-        if (ok) *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.C) + o) = pack8(c);
+        store16(r0, o2, pack8(c));
       } else if (EPI == EPI_F32) {
-        if (ok) {
-          float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + o);
-          float4 v0 = make_float4(c[0], c[1], c[2], c[3]), v1 = make_float4(c[4], c[5], c[6], c[7]);
-          if (p.accumulate) {
-            const float4 o0 = dst[0], o1 = dst[1];
-            v0.x += o0.x; v0.y += o0.y; v0.z += o0.z; v0.w += o0.w;
-            v1.x += o1.x; v1.y += o1.y; v1.z += o1.z; v1.w += o1.w;
-          }
-          dst[0] = v0;
-          dst[1] = v1;
-        }
+        // the previous value is fetched only when it is to be added to: otherwise the load is out of range and reads zero
+        const uint32_t ol = p.accumulate ? o4 : OOB;
+        const u32x4_t q0 = __builtin_amdgcn_raw_buffer_load_b128(r0, ol, 0, 0);
+        const u32x4_t q1 = __builtin_amdgcn_raw_buffer_load_b128(r0, ol, 16, 0);
+        const f32x4_t a0 = __builtin_bit_cast(f32x4_t, q0), a1 = __builtin_bit_cast(f32x4_t, q1);
+        const f32x4_t v0 = {c[0] + a0[0], c[1] + a0[1], c[2] + a0[2], c[3] + a0[3]};
+        const f32x4_t v1 = {c[4] + a1[0], c[5] + a1[1], c[6] + a1[2], c[7] + a1[3]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v0), r0, o4, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v1), r0, o4, 16, 0);
       } else {
         // e: what SiLU(G) is multiplied by: the gathered row, the up projection, or their sum
         float e[8];
@@ -620,10 +645,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
           float h[8];
 #pragma unroll
           for (int q = 0; q < 8; ++q) h[q] = c[q] * sigmoidf_fast(c[q]) * e[q];
-          if (ok) {
-            if (p.outG) *reinterpret_cast<uint4*>(p.outG + o) = pack8(c);
-            *reinterpret_cast<uint4*>(p.outH + o) = pack8(h);
-          }
+          store16(r0, o2, pack8(c));      // dropped by the hardware when G is not wanted (zero-sized buffer)
+          store16(r1, o2, pack8(h));
         } else {  // dH product
           float gz[8], du[8], dg[8];
           unpack8(gv[i & 1][pass], gz);
@@ -635,10 +658,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
             du[q] = cs * gz[q];
             dg[q] = e[q] * fmaf(du[q], 1.0f - sg, cs);
           }
-          if (ok) {
-            *reinterpret_cast<uint4*>(p.outdU + o) = pack8(du);
-            *reinterpret_cast<uint4*>(p.outdG + o) = pack8(dg);
-          }
+          store16(r0, o2, pack8(du));
+          store16(r1, o2, pack8(dg));
         }
       }
     }
@@ -691,6 +712,8 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
   const int64_t abytes = (la == OP_KC ? (int64_t)a.M : kmc) * a.lda * 2;
   const int64_t bbytes = (lb == OP_KC ? (int64_t)a.N : kmc) * a.ldb * 2;
   if (abytes > lim || bbytes > lim) return hipErrorInvalidValue;
+  // so are the outputs' (buffer stores)
+  if ((int64_t)a.M * a.N * (epi == EPI_F32 ? 4 : 2) > lim) return hipErrorInvalidValue;
   if (la == OP_KC && lb == OP_KC) {
     if (epi == EPI_BF16) return launch<OP_KC, OP_KC, EPI_BF16>(ctx, kid, a, s);
     if (epi == EPI_GATE) return launch<OP_KC, OP_KC, EPI_GATE>(ctx, kid, a, s);

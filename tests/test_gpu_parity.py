@@ -350,6 +350,83 @@ def test_edge_cases_and_error_reporting():
     ctx.close()
 
 
+def _expect_id_range(ctx):
+    with pytest.raises(L.StemError) as e:
+        L.stem_sync_status(ctx)
+    assert e.value.status == L.STEM_ERR_ID_RANGE
+    L.stem_sync_status(ctx)   # the flag was cleared
+
+
+@pytest.mark.parametrize("T,d,F", [(700, 1088, 320), (300, 128, 320)])
+def test_bf16_out_of_range_ids_are_clamped_and_reported(T, d, F):
+    """Ids outside the table on the bf16 paths: the fused epilogues of the 256x256-tile products (T = 700;
+    d_model 1088 also reaches the early touch of the gathered rows, d_ff 320 = 64 mod 128 its narrow last
+    column block) and the few-row kernel (T = 300).  No access leaves the table (an id below zero reads
+    row 0, one beyond the end the last row), the sticky flag is reported once, every output is finite,
+    and the rows of tokens with valid ids match the oracle."""
+    V = 257
+    s = inputs.StemShape("bf16-bad-ids", d, F, V, 1, T, "bf16")
+    inp = inputs.layer_inputs(s, seed=15, device=DEV, tokens=T)
+    ids_good = inp["ids"].cpu().numpy()
+    bad_at = np.array([0, 5, 63, 64, 255, 256, T - 1])
+    bad_val = np.array([V, -3, 2 ** 31 - 1, -2 ** 31, V + 7, -1, V])
+    ids_bad = ids_good.copy()
+    ids_bad[bad_at] = bad_val
+    inp_bad = dict(inp, ids=torch.from_numpy(ids_bad.astype(np.int32)).to(DEV))
+    ctx = Hn.make_ctx(s, T)
+    dt = inp["x"].dtype
+    good = np.setdiff1d(np.arange(T), bad_at)
+    f64 = {k: inputs.to_f64(v) for k, v in inp.items() if k != "ids"}
+    ref, fw = O.ffn_forward(f64["x"], ids_good, f64["W_gate"], f64["W_down"], f64["E"])
+    tol = Hn.TOL["bf16"]
+    if T <= 512:   # few-row kernel: forward only
+        y = torch.empty(T, d, dtype=dt, device=DEV)
+        G, H = (torch.empty(T, F, dtype=dt, device=DEV) for _ in range(2))
+        L.stem_ffn_forward(ctx, inp["x"], inp_bad["ids"], inp["W_gate"], inp["W_down"], inp["E"], y, G, H)
+        _expect_id_range(ctx)
+        for t in (y, G, H):
+            assert bool(torch.isfinite(t.float()).all())
+        assert Hn.max_rel(y.float().cpu().numpy()[good], ref[good]) <= tol
+        assert Hn.max_rel(H.float().cpu().numpy()[good], fw["h"][good]) <= tol
+    else:
+        out = Hn.hip_forward_backward(ctx, inp_bad)
+        _expect_id_range(ctx)
+        for t in out.values():
+            assert bool(torch.isfinite(t.float()).all())
+        bw = O.ffn_backward(f64["dy"], f64["x"], ids_good, f64["W_gate"], f64["W_down"], f64["E"])
+        for k, want in (("y", ref), ("H", fw["h"]), ("G", fw["g"]), ("dx", bw["dx"]), ("dU", bw["dU"])):
+            assert Hn.max_rel(out[k].float().cpu().numpy()[good], want[good]) <= tol, k
+        # the clamp itself: the whole result equals the oracle's on the clamped ids
+        ids_cl = np.clip(ids_bad.astype(np.int64), 0, V - 1)
+        y_cl, _ = O.ffn_forward(f64["x"], ids_cl, f64["W_gate"], f64["W_down"], f64["E"])
+        bw_cl = O.ffn_backward(f64["dy"], f64["x"], ids_cl, f64["W_gate"], f64["W_down"], f64["E"])
+        assert Hn.max_rel(out["y"].float().cpu(), y_cl) <= tol
+        assert Hn.max_rel(out["dW_gate"].cpu(), bw_cl["dW_gate"]) <= tol
+        assert Hn.max_rel(out["dW_down"].cpu(), bw_cl["dW_down"]) <= tol
+    ctx.close()
+
+
+@pytest.mark.parametrize("T", [16384, 20000])
+def test_sort_paths_clamp_and_report_out_of_range_ids(T):
+    """The one-workgroup sort (T = 16384) and the multi-kernel sort (T = 20000) with ids outside the
+    table: the flag is raised, and sort, unique, offsets and the row sums are those of the clamped ids."""
+    V, F = 5000, 64
+    s = inputs.StemShape("bf16-bad-sort", 64, F, V, 1, T, "bf16")
+    ids = inputs.zipf_ids(T, V, seed=16).astype(np.int64)
+    ids[[0, 7, 1023, 1024, T // 2, T - 1]] = [V, -1, 2 ** 31 - 1, -2 ** 31, V + 100, -77]
+    ids32 = ids.astype(np.int32)
+    ctx = Hn.make_ctx(s, T)
+    dU = inputs.normal((T, F), 1.0, 17, torch.bfloat16, DEV)
+    eg = Hn.hip_embed_grad(ctx, torch.from_numpy(ids32).to(DEV), dU, V)
+    _expect_id_range(ctx)
+    ids_cl = np.clip(ids, 0, V - 1).astype(np.int32)
+    U = Hn.check_integers(eg, ids_cl)
+    oeg = O.embed_grad(ids_cl, inputs.to_f64(dU))
+    assert bool(torch.isfinite(eg["dE_rows"][:U]).all())
+    assert Hn.max_rel(eg["dE_rows"][:U].cpu(), oeg["dE_rows"]) <= 1e-5
+    ctx.close()
+
+
 def test_id_at_last_row_of_table():
     s = inputs.StemShape("lastrow", 64, 64, 33, 1, 40, "bf16")
     ids = np.full(40, 32, np.int32)

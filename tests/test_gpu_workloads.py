@@ -1,5 +1,6 @@
-"""GPU parity at the full workload sizes (sampled outputs the oracle can compute one by one),
-the stacked decode chain, and the host-resident-table mode.  All through the C ABI."""
+"""GPU parity at the full workload sizes (every element of C2 and C3 against a whole-batch oracle run;
+sampled tokens for the 65536-token host-resident case), the stacked decode chain, and the
+host-resident-table mode.  All through the C ABI."""
 import os
 
 import numpy as np
@@ -20,10 +21,10 @@ def _rows(t, idx):
 
 
 def _full_size_case(name, seed):
-    """Whole hot path in the launch configuration bench.py times; the oracle is evaluated
-    (a) on sampled tokens with all features: y, G, H, dx, dU rows;
-    (b) on sampled features with all tokens: columns of dW_down, rows of dW_gate, columns of the
-        table gradient and of the AdamW state.  Both are exact restrictions of the layer."""
+    """Whole hot path in the launch configuration bench.py times, against one run of the oracle over
+    the whole batch: every element of y, G, H, dx, dU, dW_gate, dW_down and of the table-gradient
+    rows is compared.  (The oracle works on the table cut down to the rows the batch names, which
+    leaves the layer unchanged.)"""
     shape = inputs.SHAPES[name]
     T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
     tol = Hn.TOL[shape.dtype]
@@ -35,36 +36,32 @@ def _full_size_case(name, seed):
     ids = inp["ids"].cpu().numpy()
     U = Hn.check_integers(eg, ids)
 
-    rng = np.random.default_rng(seed)
-    # (a) token sample: first, last, tile borders, random
-    tok = np.unique(np.concatenate([[0, 1, 255, 256, 257, T - 257, T - 256, T - 1], rng.integers(0, T, 40)]))
-    uniq_t, remap_t = np.unique(ids[tok], return_inverse=True)
-    E_t = _rows(inp["E"], uniq_t)
-    Wg, Wd = inputs.to_f64(inp["W_gate"]), inputs.to_f64(inp["W_down"])
-    x_t, dy_t = _rows(inp["x"], tok), _rows(inp["dy"], tok)
-    y, fw = O.ffn_forward(x_t, remap_t, Wg, Wd, E_t)
-    bw = O.ffn_backward(dy_t, x_t, remap_t, Wg, Wd, E_t)
-    errs = {
-        "y": Hn.max_rel(_rows(out["y"], tok), y), "G": Hn.max_rel(_rows(out["G"], tok), fw["g"]),
-        "H": Hn.max_rel(_rows(out["H"], tok), fw["h"]), "dx": Hn.max_rel(_rows(out["dx"], tok), bw["dx"]),
-        "dU": Hn.max_rel(_rows(out["dU"], tok), bw["dU"]),
-    }
-    # (b) feature sample, all tokens
-    fs = np.unique(np.concatenate([[0, 1, 255, 256, F - 1], rng.integers(0, F, 27)]))
-    fs_t = torch.as_tensor(fs, device=DEV)
     uniq_all, remap_all = np.unique(ids, return_inverse=True)
-    E_f = inputs.to_f64(inp["E"][torch.as_tensor(uniq_all.astype(np.int64), device=DEV)][:, fs_t])
+    E_u = _rows(inp["E"], uniq_all)
+    Wg, Wd = inputs.to_f64(inp["W_gate"]), inputs.to_f64(inp["W_down"])
     x_all, dy_all = inputs.to_f64(inp["x"]), inputs.to_f64(inp["dy"])
-    bwf = O.ffn_backward(dy_all, x_all, remap_all, Wg[fs], Wd[:, fs], E_f)
-    errs["dW_gate"] = Hn.max_rel(inputs.to_f64(out["dW_gate"][fs_t]), bwf["dW_gate"])
-    errs["dW_down"] = Hn.max_rel(inputs.to_f64(out["dW_down"][:, fs_t]), bwf["dW_down"])
-    oeg = O.embed_grad(ids, bwf["dU"])
+    y, fw = O.ffn_forward(x_all, remap_all, Wg, Wd, E_u)
+    errs = {"y": Hn.max_rel(inputs.to_f64(out["y"]), y), "G": Hn.max_rel(inputs.to_f64(out["G"]), fw["g"]),
+            "H": Hn.max_rel(inputs.to_f64(out["H"]), fw["h"])}
+    del y, fw
+    bw = O.ffn_backward(dy_all, x_all, remap_all, Wg, Wd, E_u)
+    errs["dx"] = Hn.max_rel(inputs.to_f64(out["dx"]), bw["dx"])
+    errs["dU"] = Hn.max_rel(inputs.to_f64(out["dU"]), bw["dU"])
+    errs["dW_gate"] = Hn.max_rel(inputs.to_f64(out["dW_gate"]), bw["dW_gate"])
+    errs["dW_down"] = Hn.max_rel(inputs.to_f64(out["dW_down"]), bw["dW_down"])
+    oeg = O.embed_grad(ids, bw["dU"])
+    del bw
     np.testing.assert_array_equal(oeg["uniq_ids"], uniq_all)
-    errs["dE_rows"] = Hn.max_rel(inputs.to_f64(eg["dE_rows"][:U][:, fs_t]), oeg["dE_rows"])
+    errs["dE_rows"] = Hn.max_rel(inputs.to_f64(eg["dE_rows"][:U]), oeg["dE_rows"])
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, f"{name}: over tolerance {tol}: {bad} (all: {errs})"
-    print(name, "max-relative errors", {k: float("%.3g" % v) for k, v in errs.items()}, "n_uniq", U)
+    print(name, "max-relative errors over all elements", {k: float("%.3g" % v) for k, v in errs.items()}, "n_uniq", U)
 
+    # the optimiser state is compared on a sample of features (all touched rows)
+    rng = np.random.default_rng(seed)
+    fs = np.unique(np.concatenate([[0, 1, 255, 256, F - 1], rng.integers(0, F, 27)]))
+    fs_t = torch.as_tensor(fs, device=DEV)
+    oeg = {"dE_rows": oeg["dE_rows"][:, fs]}
     # sparse AdamW on the touched rows (own gradients on each side; see the small-size test for why
     # parameters are compared where the gradient's sign is certain)
     E = inp["E"]

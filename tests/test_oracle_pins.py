@@ -434,6 +434,35 @@ def test_lfu_row_cache_serves_right_rows_and_keeps_the_most_frequent():
     assert 0.5 < hit_tokens / total < 0.75, hit_tokens / total
 
 
+def test_lfu_row_cache_hand_worked_tie_breaks():
+    """Four batches worked out by hand from the stated policy (3 slots, ids below 10): every remap,
+    miss list and slot content is written out here, not computed.  The batches are chosen so that the
+    order of equally frequent candidates (id ascending) and of equally cold victims (id ascending)
+    decides the outcome, and so that a candidate which fails ends the update."""
+    c = O.LfuRowCache(10, 3)
+    # batch 1: empty cache, everything misses in order of first use; counts 5:3, 3:2, 7:1, 9:1.
+    # Offered 5, 3, then 7 before 9 (equal counts, lower id first): 7 takes the last free slot,
+    # 9 finds neither a free slot nor a cached row the batch did not use, and the update ends.
+    remap, misses, installs = c.step([5, 3, 5, 7, 3, 5, 9])
+    assert remap.tolist() == [3, 4, 3, 5, 4, 3, 6] and misses.tolist() == [5, 3, 7, 9]
+    assert installs == [(5, 0, 0), (3, 1, 1), (7, 2, 2)] and c.id_in_slot == [5, 3, 7]
+    # batch 2: 5 hits slot 0; misses 9, 2, 8.  Counts now 9:3, 8:2, 2:1, 5:4; cached and unused: 7 (1), 3 (2).
+    # 9 (3) replaces the coldest, 7; 8 (2) is not strictly more frequent than 3 (2): it fails, the update ends.
+    remap, misses, installs = c.step([9, 9, 2, 5, 8, 8])
+    assert remap.tolist() == [3, 3, 4, 0, 5, 5] and misses.tolist() == [9, 2, 8]
+    assert installs == [(9, 2, 0)] and c.id_in_slot == [5, 3, 9]
+    # batch 3: misses 6, 1, 4 with counts 6:3, 1:3, 4:1; cached and unused: 3 (2), 9 (3), 5 (4).
+    # Equal counts: 1 is offered before 6 and replaces 3; 6 (3) is not above 9 (3) and fails.
+    remap, misses, installs = c.step([6, 6, 6, 1, 1, 1, 4])
+    assert remap.tolist() == [3, 3, 3, 4, 4, 4, 5] and misses.tolist() == [6, 1, 4]
+    assert installs == [(1, 1, 1)] and c.id_in_slot == [5, 1, 9]
+    # batch 4: 6 reaches count 5; cached and unused: 1 (3), 9 (3), 5 (4).  Equally cold: the lower id, 1, goes.
+    remap, misses, installs = c.step([6, 6])
+    assert remap.tolist() == [3, 3] and misses.tolist() == [6]
+    assert installs == [(6, 1, 0)] and c.id_in_slot == [5, 6, 9]
+    assert c.freq.tolist() == [0, 3, 1, 2, 1, 4, 5, 1, 2, 3]
+
+
 def test_edit_target_index_follows_the_stated_rules():
     # one to one; left padding; "each target token repeated floor(n_s / n_t) times, the last one
     # repeated as needed to cover the n_s source positions"
