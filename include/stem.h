@@ -131,6 +131,30 @@ stem_status stem_embed_grad(stem_ctx* ctx, const int32_t* ids, const void* dU, i
                             int32_t* sorted_ids, int32_t* perm, int32_t* uniq_ids,
                             int32_t* seg_offsets, int32_t* n_uniq, float* dE_rows, void* stream);
 
+/* stem_embed_grad for callers that cannot allocate device memory: code under HIP graph capture,
+ * serving loops and harnesses that forbid hipMalloc.  It needs no context: the scratch that
+ * stem_embed_grad takes from its context (run indices, sort buffers, partial sums of runs that
+ * cross chunk borders) lives in one static device array of about 33 MiB that every GPU the library
+ * runs on holds from the moment the library is loaded until the process ends.  The call allocates
+ * and frees nothing.  It works on the CURRENT device (hipSetDevice is the caller's business); its
+ * first call on a device looks the array's address up (make that call outside a stream capture).
+ * dtype, vocab, d_ff: as in stem_layer_desc (d_ff a multiple of 8 for STEM_BF16, of 4 for STEM_F32).
+ * All other arguments and all results are those of stem_embed_grad.  id_flag (device int32, may be
+ * NULL) is set to 1 when an id outside [0, vocab) is seen (such ids are clamped as everywhere); it is
+ * never cleared by the library, and with NULL the report is lost.
+ * Limits: T <= STEM_NOALLOC_MAX_TOKENS and, when dE_rows is wanted, ceil(T/32) * 8 * d_ff bytes of
+ * partial sums <= STEM_NOALLOC_PART_BYTES (T * d_ff <= 2^27: the 1B-shaped layer at 16384 tokens just
+ * fits); larger calls return STEM_ERR_SHAPE with the limit in stem_last_error(NULL).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race; calls on one stream, or ordered by events, are safe.  Nothing in the array has
+ * to be cleared between calls: every word a call reads it has written itself. */
+#define STEM_NOALLOC_MAX_TOKENS 65536
+#define STEM_NOALLOC_PART_BYTES (32u << 20)
+stem_status stem_embed_grad_noalloc(int32_t dtype, int32_t vocab, int32_t d_ff, const int32_t* ids,
+                                    const void* dU, int64_t T, int32_t* sorted_ids, int32_t* perm,
+                                    int32_t* uniq_ids, int32_t* seg_offsets, int32_t* n_uniq, float* dE_rows,
+                                    int32_t* id_flag, void* stream);
+
 /* ---- optimiser: AdamW on the touched rows only --------------------------------- */
 
 /* For each j < *n_uniq, row r = uniq_ids[j], element-wise with g = dE_rows[j]:

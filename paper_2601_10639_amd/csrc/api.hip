@@ -22,14 +22,7 @@ const char* const kKernelNames[K_COUNT_] = {
     "sort_fused",      "unique",          "seg_reduce",   "seg_combine",   "sparse_adamw", "row_copy",
     "transpose",       "splitk_reduce",   "gemm_up",      "gemm_dw_up"};
 
-stem_status fail(stem_ctx* c, stem_status st, const char* fmt, ...) {
-  char* buf = c ? c->err : g_create_err;
-  va_list ap;
-  va_start(ap, fmt);
-  vsnprintf(buf, 512, fmt, ap);
-  va_end(ap);
-  return st;
-}
+#define fail stem_fail
 
 #define HIP_TRY(c, expr)                                                                     \
   do {                                                                                       \
@@ -98,7 +91,24 @@ void release(stem_ctx* c) {
   free(c);
 }
 
+EmbedScratch embed_scratch(const stem_ctx* c) {
+  EmbedScratch w;
+  w.sort_keys[0] = c->sort_keys[0]; w.sort_keys[1] = c->sort_keys[1];
+  w.sort_vals[0] = c->sort_vals[0]; w.sort_vals[1] = c->sort_vals[1];
+  w.sort_counts = c->sort_counts; w.seg_of = c->seg_of; w.seg_part = c->seg_part; w.flag = c->flag;
+  return w;
+}
+
 }  // namespace
+
+stem_status stem_fail(stem_ctx* c, stem_status st, const char* fmt, ...) {
+  char* buf = c ? c->err : g_create_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, 512, fmt, ap);
+  va_end(ap);
+  return st;
+}
 
 extern "C" {
 
@@ -519,9 +529,10 @@ stem_status stem_embed_grad(stem_ctx* c, const int32_t* ids, const void* dU, int
     return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: dU and dE_rows must both be given or both be NULL");
   if (misaligned(dU) || misaligned(dE_rows))
     return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: dU and dE_rows must be 16-byte aligned");
-  HIP_TRY(c, stem_sort_unique(c, ids, T, c->desc.vocab, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, s));
+  const EmbedScratch ws = embed_scratch(c);
+  HIP_TRY(c, stem_sort_unique(c, ws, ids, T, c->desc.vocab, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, s));
   if (dU)
-    HIP_TRY(c, stem_seg_reduce(c, c->desc.dtype == STEM_BF16, dU, perm, seg_offsets, T, c->desc.d_ff, dE_rows, s));
+    HIP_TRY(c, stem_seg_reduce(c, ws, c->desc.dtype == STEM_BF16, dU, perm, seg_offsets, T, c->desc.d_ff, dE_rows, s));
   return STEM_OK;
 }
 

@@ -508,15 +508,15 @@ int64_t stem_sort_count_entries(int64_t max_tokens) {
   return tiles * SORT_WAVES * RADIX;
 }
 
-hipError_t stem_sort_unique(stem_ctx* ctx, const int32_t* ids, int64_t T, int V, int32_t* sorted_ids,
-                            int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets, int32_t* n_uniq,
-                            hipStream_t s) {
+hipError_t stem_sort_unique(stem_ctx* ctx, const EmbedScratch& ws, const int32_t* ids, int64_t T, int V,
+                            int32_t* sorted_ids, int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets,
+                            int32_t* n_uniq, hipStream_t s) {
   const int passes = (bits_for(V) + RADIX_BITS - 1) / RADIX_BITS;
   const int pos_bits = bits_for((int)T);
   if (T <= FUSED_MAX_T && bits_for(V) + pos_bits <= 32) {
     ProfScope ps(ctx, K_SORT_FUSED, s);
     hipLaunchKernelGGL(sort_unique_fused_kernel, dim3(1), dim3(1024), 0, s, ids, (int)T, V, pos_bits, passes,
-                       sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, ctx->seg_of, ctx->flag);
+                       sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, ws.seg_of, ws.flag);
     return hipGetLastError();
   }
   const int tiles = (int)((T + SORT_TILE - 1) / SORT_TILE);
@@ -524,22 +524,22 @@ hipError_t stem_sort_unique(stem_ctx* ctx, const int32_t* ids, int64_t T, int V,
   const int32_t* src_k = ids;
   const int32_t* src_v = nullptr;
   for (int p = 0; p < passes; ++p) {
-    int32_t* dst_k = (p == passes - 1) ? sorted_ids : ctx->sort_keys[p & 1];
-    int32_t* dst_v = (p == passes - 1) ? perm : ctx->sort_vals[p & 1];
+    int32_t* dst_k = (p == passes - 1) ? sorted_ids : ws.sort_keys[p & 1];
+    int32_t* dst_v = (p == passes - 1) ? perm : ws.sort_vals[p & 1];
     const int shift = p * RADIX_BITS;
     {
       ProfScope ps(ctx, K_SORT_COUNT, s);
       hipLaunchKernelGGL(sort_count_kernel, dim3(tiles), dim3(1024), 0, s, src_k, T, V, shift, p == 0, nW,
-                         ctx->sort_counts, ctx->flag);
+                         ws.sort_counts, ws.flag);
     }
     {
       ProfScope ps(ctx, K_SORT_SCAN, s);
-      hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, s, ctx->sort_counts, nW * RADIX);
+      hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, s, ws.sort_counts, nW * RADIX);
     }
     {
       ProfScope ps(ctx, K_SORT_SCATTER, s);
       hipLaunchKernelGGL(sort_scatter_kernel, dim3(tiles), dim3(1024), 0, s, src_k, src_v, T, V, shift, p == 0,
-                         nW, ctx->sort_counts, dst_k, dst_v, ctx->flag);
+                         nW, ws.sort_counts, dst_k, dst_v, ws.flag);
     }
     src_k = dst_k;
     src_v = dst_v;
@@ -547,12 +547,12 @@ hipError_t stem_sort_unique(stem_ctx* ctx, const int32_t* ids, int64_t T, int V,
   {
     ProfScope ps(ctx, K_UNIQUE, s);
     hipLaunchKernelGGL(unique_kernel, dim3(1), dim3(1024), 0, s, sorted_ids, T, uniq_ids, seg_offsets, n_uniq,
-                       ctx->seg_of);
+                       ws.seg_of);
   }
   return hipGetLastError();
 }
 
-hipError_t stem_seg_reduce(stem_ctx* ctx, int is_bf16, const void* dU, const int32_t* perm,
+hipError_t stem_seg_reduce(stem_ctx* ctx, const EmbedScratch& ws, int is_bf16, const void* dU, const int32_t* perm,
                            const int32_t* seg_offsets, int64_t T, int F, float* dE_rows, hipStream_t s) {
   const int chunks = (int)((T + SEG_ROWS - 1) / SEG_ROWS);
   const int cols = is_bf16 ? 8 : 4;
@@ -560,20 +560,20 @@ hipError_t stem_seg_reduce(stem_ctx* ctx, int is_bf16, const void* dU, const int
   {
     ProfScope ps(ctx, K_SEG_REDUCE, s);
     if (is_bf16)
-      hipLaunchKernelGGL(seg_reduce_kernel<true>, dim3(slabs, chunks), dim3(256), 0, s, dU, perm, ctx->seg_of, T, F,
-                         dE_rows, ctx->seg_part);
+      hipLaunchKernelGGL(seg_reduce_kernel<true>, dim3(slabs, chunks), dim3(256), 0, s, dU, perm, ws.seg_of, T, F,
+                         dE_rows, ws.seg_part);
     else
-      hipLaunchKernelGGL(seg_reduce_kernel<false>, dim3(slabs, chunks), dim3(256), 0, s, dU, perm, ctx->seg_of, T,
-                         F, dE_rows, ctx->seg_part);
+      hipLaunchKernelGGL(seg_reduce_kernel<false>, dim3(slabs, chunks), dim3(256), 0, s, dU, perm, ws.seg_of, T,
+                         F, dE_rows, ws.seg_part);
   }
   {
     ProfScope ps(ctx, K_SEG_COMBINE, s);
     if (is_bf16)
-      hipLaunchKernelGGL(seg_combine_kernel<8>, dim3(chunks, slabs), dim3(256), 0, s, ctx->seg_of, seg_offsets, T,
-                         F, dE_rows, ctx->seg_part);
+      hipLaunchKernelGGL(seg_combine_kernel<8>, dim3(chunks, slabs), dim3(256), 0, s, ws.seg_of, seg_offsets, T,
+                         F, dE_rows, ws.seg_part);
     else
-      hipLaunchKernelGGL(seg_combine_kernel<4>, dim3(chunks, slabs), dim3(256), 0, s, ctx->seg_of, seg_offsets, T,
-                         F, dE_rows, ctx->seg_part);
+      hipLaunchKernelGGL(seg_combine_kernel<4>, dim3(chunks, slabs), dim3(256), 0, s, ws.seg_of, seg_offsets, T,
+                         F, dE_rows, ws.seg_part);
   }
   return hipGetLastError();
 }

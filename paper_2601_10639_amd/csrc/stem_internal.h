@@ -189,13 +189,25 @@ hipError_t stem_dh_epilogue_f32(stem_ctx* ctx, const float* dH, const float* G, 
                                 hipStream_t s);
 
 // ---- table gradient (embed_grad.hip) ----------------------------------------------
-hipError_t stem_sort_unique(stem_ctx* ctx, const int32_t* ids, int64_t T, int V, int32_t* sorted_ids,
-                            int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets, int32_t* n_uniq,
-                            hipStream_t s);
-hipError_t stem_seg_reduce(stem_ctx* ctx, int is_bf16, const void* dU, const int32_t* perm,
+// Device scratch of the sort and the segmented sum: a context's own buffers, or pieces of the
+// library's static scratch array (the entry point that allocates nothing).
+struct EmbedScratch {
+  int32_t* sort_keys[2]; // [T] each (multi-kernel sort only)
+  int32_t* sort_vals[2]; // [T] each
+  int32_t* sort_counts;  // [stem_sort_count_entries(T)]
+  int32_t* seg_of;       // [T] index of the run each sorted position is in
+  float* seg_part;       // [stem_seg_chunks(T)][2][F] partial sums of runs that cross chunk borders
+  int32_t* flag;         // sticky id-range flag (host-pinned or device)
+};
+hipError_t stem_sort_unique(stem_ctx* prof, const EmbedScratch& ws, const int32_t* ids, int64_t T, int V,
+                            int32_t* sorted_ids, int32_t* perm, int32_t* uniq_ids, int32_t* seg_offsets,
+                            int32_t* n_uniq, hipStream_t s);
+hipError_t stem_seg_reduce(stem_ctx* prof, const EmbedScratch& ws, int is_bf16, const void* dU, const int32_t* perm,
                            const int32_t* seg_offsets, int64_t T, int F, float* dE_rows, hipStream_t s);
 int64_t stem_seg_chunks(int64_t max_tokens);
 int64_t stem_sort_count_entries(int64_t max_tokens);
+// error text for calls that have no context (stem_last_error(NULL) returns it)
+stem_status stem_fail(stem_ctx* c, stem_status st, const char* fmt, ...);
 
 // ---- optimiser (adamw.hip) ----------------------------------------------------------
 hipError_t stem_adamw(stem_ctx* ctx, int is_bf16, const int32_t* uniq_ids, const int32_t* n_uniq,

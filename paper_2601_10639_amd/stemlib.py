@@ -22,7 +22,7 @@ STEM_F32, STEM_BF16 = 0, 1
 SYMBOLS = [
     "stem_create", "stem_destroy", "stem_last_error", "stem_status_string", "stem_sync_status",
     "stem_ffn_forward", "stem_ffn_backward", "stem_ffn_up_forward", "stem_ffn_up_backward",
-    "stem_embed_grad", "stem_embed_sparse_adamw",
+    "stem_embed_grad", "stem_embed_grad_noalloc", "stem_embed_sparse_adamw",
     "stem_prefetch_rows", "stem_cache_init", "stem_prefetch_rows_cached", "stem_cache_state",
     "stem_edit_rows", "stem_profile_enable", "stem_profile_kernels", "stem_profile_read",
     "stem_profile_reset",
@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.stem_ffn_up_backward.restype = i32
         L.stem_embed_grad.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
         L.stem_embed_grad.restype = i32
+        L.stem_embed_grad_noalloc.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.stem_embed_grad_noalloc.restype = i32
         L.stem_embed_sparse_adamw.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp,
                                               ctypes.POINTER(stem_adamw_hparams), vp]
         L.stem_embed_sparse_adamw.restype = i32
@@ -248,6 +250,20 @@ def stem_embed_grad(ctx: StemCtx, ids, dU, sorted_ids, perm, uniq_ids, seg_offse
                                _ptr(n_uniq, i32, name="n_uniq"), _ptr(dE_rows, torch.float32, name="dE_rows"),
                                _stream(stream))
     _check(ctx, st, "stem_embed_grad")
+
+
+def stem_embed_grad_noalloc(dtype: int, vocab: int, d_ff: int, ids, dU, sorted_ids, perm, uniq_ids, seg_offsets,
+                            n_uniq, dE_rows, id_flag=None, stream=None, T=None):
+    """stem_embed_grad on the library's static scratch: no context, no allocation; current device."""
+    i32 = torch.int32
+    T = ids.shape[0] if T is None else T
+    dt = torch.bfloat16 if dtype == STEM_BF16 else torch.float32
+    st = lib().stem_embed_grad_noalloc(dtype, vocab, d_ff, _ptr(ids, i32, name="ids"), _ptr(dU, dt, name="dU"), T,
+                                       _ptr(sorted_ids, i32, name="sorted_ids"), _ptr(perm, i32, name="perm"),
+                                       _ptr(uniq_ids, i32, name="uniq_ids"), _ptr(seg_offsets, i32, name="seg_offsets"),
+                                       _ptr(n_uniq, i32, name="n_uniq"), _ptr(dE_rows, torch.float32, name="dE_rows"),
+                                       _ptr(id_flag, i32, name="id_flag"), _stream(stream))
+    _check(None, st, "stem_embed_grad_noalloc")
 
 
 def stem_embed_sparse_adamw(ctx: StemCtx, uniq_ids, n_uniq, dE_rows, E, master, m, v, lr, beta1, beta2, eps,
