@@ -32,8 +32,8 @@ PEAK_HBM_GBS = 8000.0
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--ids", default="zipf", choices=["zipf", "uniform"], help="id distribution for C5")
     ap.add_argument("--cache-slots", type=int, default=0,
@@ -46,6 +46,10 @@ def main() -> int:
                     help="stem: the STEM layer (the headline); dense: SwiGLU FFN with an up projection and no table; "
                          "additive: up projection plus table (C2, C3 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the short runs of the other configurations (C2, C4, C5) reported under 'secondary'")
+    ap.add_argument("--no-overlap-sort", action="store_true",
+                    help="run the integer half of the table gradient in line instead of on a second stream under the backward products")
     ap.add_argument("--cpu-sample-tokens", type=int, default=16384)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -55,7 +59,6 @@ def main() -> int:
               file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
 
     from paper_2601_10639_amd import inputs, stemlib as L
@@ -67,11 +70,80 @@ def main() -> int:
     dev = "cuda:0"
     shape = inputs.SHAPES[args.workload]
     if args.workload == "C4":
-        return bench_decode(args, shape, dev)
+        print(json.dumps(bench_decode(args, shape, dev)))
+        return 0
     if args.workload == "C5":
-        return bench_host_table(args, shape, dev)
+        print(json.dumps(bench_host_table(args, shape, dev, [args.ids])[args.ids]))
+        return 0
     if args.host_state:
         return bench_host_training(args, shape, dev)
+    peaks = measure_peaks(dev)
+    out, inp = bench_layer(args, shape, dev, args.steps, args.warmup, peaks, detail=True)
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    if args.variant == "stem" and args.workload == "C3" and not args.no_secondary:
+        del inp["E"]
+        torch.cuda.empty_cache()
+        out["secondary"] = secondary_runs(args, dev, peaks)
+        inp = None
+    if not args.no_cpu_baseline and args.variant == "stem":
+        if inp is None:   # same seed: the same batch again
+            inp = inputs.layer_inputs(shape, seed=3, device=dev)
+        out["cpu_baseline"] = cpu_baseline(shape, inp, args.cpu_sample_tokens, hp)
+    print(json.dumps(out))
+    return 0
+
+
+def measure_peaks(dev):
+    """What this machine sustains: an MFMA-only loop, a streaming read and a streaming copy of 1 GiB
+    (kernels in csrc/calibrate.hip).  The roofline fractions keep the published peaks as denominators;
+    `frac_of_measured` next to them uses these."""
+    import torch
+
+    from paper_2601_10639_amd import stemlib as L
+    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    b = torch.empty_like(a)
+    peaks = {
+        "mfma_bf16_tflops": round(L.stem_measure_peak(L.STEM_PEAK_MFMA_BF16, a, None, repeats=3), 1),
+        "hbm_read_gbs": round(L.stem_measure_peak(L.STEM_PEAK_HBM_READ, a, b, repeats=5), 1),
+        "hbm_copy_gbs": round(L.stem_measure_peak(L.STEM_PEAK_HBM_COPY, a, b, repeats=5), 1),
+        "how": "stem_measure_peak: loop of independent 32x32x16 bf16 MFMAs on registers (7 ms); 1 GiB streaming read; "
+               "1 GiB streaming copy, bytes read + written; best of 3 / 5 / 5 runs between HIP events",
+    }
+    del a, b
+    torch.cuda.empty_cache()
+    return peaks
+
+
+def _dist(ms_list):
+    import numpy as np
+    ts = np.sort(np.asarray(ms_list, dtype=np.float64))
+    return {"median": round(float(np.median(ts)), 4), "p10": round(float(ts[int(0.1 * (len(ts) - 1))]), 4),
+            "p90": round(float(ts[int(round(0.9 * (len(ts) - 1)))]), 4), "n": int(len(ts))}
+
+
+def _event_times(fn, n, warmup):
+    """Per-call device time in ms between HIP events recorded on torch's current stream (the stream
+    the library launches on) right before and right after each call; calls run back to back."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for e0, e1 in evs:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    return [e0.elapsed_time(e1) for e0, e1 in evs]
+
+
+def bench_layer(args, shape, dev, steps, warmup, peaks, detail):
+    """One layer's training step (forward, backward, table gradient, sparse AdamW) at `shape`.
+    Returns (the JSON object, the inputs)."""
+    import torch
+
+    from paper_2601_10639_amd import inputs, stemlib as L
+
     T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
     bf16 = shape.dtype == "bf16"
     dt = inputs.torch_dtype(shape.dtype)
@@ -103,14 +175,18 @@ def main() -> int:
     variant = args.variant
     if variant != "stem":
         if not bf16:
-            print("bench.py: --variant dense/additive needs a bf16 workload (C2, C3)", file=sys.stderr)
-            return 2
+            raise SystemExit("bench.py: --variant dense/additive needs a bf16 workload (C2, C3)")
         W_up = inputs.normal((F, d), 0.02, 3004, dt, dev)
         Up = torch.empty(T, F, dtype=dt, device=dev)
         dWu = torch.empty(F, d, dtype=torch.float32, device=dev)
+    # The integer half of the table gradient (sort, distinct ids, offsets) needs the token ids only:
+    # it is enqueued on a second stream after the forward call and joins the main stream before the
+    # row sums, so its one workgroup runs in the gaps of the backward products.
+    overlap_sort = variant == "stem" and not args.no_overlap_sort
+    main_stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream() if overlap_sort else None
 
-    def step():
-        step_no[0] += 1
+    def fwd_bwd():
         if variant == "stem":
             L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, y, G, H)
             L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, H, dx, dWg,
@@ -120,43 +196,70 @@ def main() -> int:
             L.stem_ffn_up_forward(ctx, inp["x"], tid, inp["W_gate"], W_up, inp["W_down"], tab, y, G, Up, H)
             L.stem_ffn_up_backward(ctx, inp["dy"], inp["x"], tid, inp["W_gate"], W_up, inp["W_down"], tab, G, Up, H,
                                    dx, dWg, dWu, dWd, dU)
+
+    def step():
+        step_no[0] += 1
+        if overlap_sort:
+            L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, y, G, H)
+            side.wait_stream(main_stream)      # after the previous step's optimiser, which reads uniq_ids / n_uniq
+            L.stem_embed_grad(ctx, inp["ids"], None, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, None, stream=side)
+            L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, H, dx, dWg,
+                                dWd, dU)
+            main_stream.wait_stream(side)
+            L.stem_embed_grad_presorted(ctx, dU, perm, seg_offsets, dE_rows)
+            L.stem_embed_sparse_adamw(ctx, uniq_ids, n_uniq, dE_rows, E, master, m, v, step=step_no[0], **hp)
+            return
+        fwd_bwd()
         if variant != "dense":
             L.stem_embed_grad(ctx, inp["ids"], dU, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, dE_rows)
             L.stem_embed_sparse_adamw(ctx, uniq_ids, n_uniq, dE_rows, E, master, m, v, step=step_no[0], **hp)
 
-    if args.calibrate_copy:
+    if args.calibrate_copy and detail:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    # the contract's figure: W untimed steps, then exactly K steps between two synchronisations
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     L.stem_sync_status(ctx)
-    ms_per_step = elapsed / args.steps * 1e3
-    tokens_per_s = T * args.steps / elapsed
+    ms_per_step = elapsed / steps * 1e3
+    tokens_per_s = T * steps / elapsed
     U = int(n_uniq.item()) if variant != "dense" else 0
+
+    # the same step, and forward + backward alone, timed call by call between HIP events: at least 50 calls
+    n_dist = max(50, steps)
+    step_dist = _dist(_event_times(step, n_dist, 3))
+    fb_dist = _dist(_event_times(fwd_bwd, n_dist, 3))
 
     # Per-kernel durations: the same K steps again with HIP events around every launch, on the
     # stream the kernels run on.
     L.stem_profile_enable(ctx, True)
     L.stem_profile_reset(ctx)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     prof = L.stem_profile_read(ctx)
+    # the stand-alone SiLU * gather kernel at this shape (what backward runs when H was not saved)
+    if variant == "stem":
+        L.stem_profile_reset(ctx)
+        for _ in range(10):
+            L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, None, dx, dWg,
+                                dWd, dU)
+        prof["silu_gather"] = L.stem_profile_read(ctx)["silu_gather"]
     L.stem_profile_enable(ctx, False)
+    L.stem_sync_status(ctx)
 
     gemm_flop = 2.0 * T * d * F
     peak_tf = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
     es = 2 if bf16 else 4
     algo_bytes = {
-        "seg_reduce": T * F * es + U * F * 4,
         "sparse_adamw": U * F * (30 if bf16 else 28),
         "silu_gather": 2 * T * F * es + U * F * es,
     }
@@ -168,26 +271,40 @@ def main() -> int:
             fl = gemm_flop * (2 if (name == "gemm_dx" and variant != "stem") else 1)   # dx spans both projections
             k["tflops"] = round(fl / (avg * 1e-3) / 1e12, 2)
             k["frac_mfma_peak"] = round(k["tflops"] / peak_tf, 4)
+            if bf16:
+                k["frac_of_measured"] = round(k["tflops"] / peaks["mfma_bf16_tflops"], 4)
         elif name in algo_bytes:
+            k["algorithmic_bytes"] = algo_bytes[name]
             k["gbs"] = round(algo_bytes[name] / (avg * 1e-3) / 1e9, 1)
             k["frac_hbm_peak"] = round(k["gbs"] / PEAK_HBM_GBS, 4)
+            k["frac_of_measured_copy"] = round(k["gbs"] / peaks["hbm_copy_gbs"], 4)
         kernels[name] = k
-    # measured HBM-side bytes per launch (rocprofv3 FETCH_SIZE / WRITE_SIZE), if a summary for this workload is committed
-    traffic = {}
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % shape.name.replace("-", "_"))
-    if os.path.exists(tpath):
-        with open(tpath) as fh:
+    # the segmented sum (G3) is everything it launches: the chunk sums and the sums over border-crossing runs
+    if "seg_reduce" in kernels:
+        g3_ms = kernels["seg_reduce"]["avg_ms"] + kernels.get("seg_combine", {"avg_ms": 0.0})["avg_ms"]
+        g3_bytes = T * F * es + U * F * 4
+        kernels["table_grad_G3"] = {
+            "avg_ms": round(g3_ms, 5), "is": "seg_reduce + seg_combine", "algorithmic_bytes": g3_bytes,
+            "gbs": round(g3_bytes / (g3_ms * 1e-3) / 1e9, 1),
+            "frac_hbm_peak": round(g3_bytes / (g3_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "frac_of_measured_copy": round(g3_bytes / (g3_ms * 1e-3) / 1e9 / peaks["hbm_copy_gbs"], 4)}
+    # measured HBM-side bytes per launch (rocprofv3 FETCH_SIZE / WRITE_SIZE) and MFMA-busy fraction / sustained
+    # shader clock per kernel: read from the summaries committed under profiles/ (another run of this command on a
+    # box of the same pool, not this run)
+    traffic, counters = {}, {}
+    tname = "hbm_traffic_%s.json" % shape.name.replace("-", "_")
+    cname = "mfma_util_%s.json" % shape.name.replace("-", "_")
+    if os.path.exists(os.path.join(ROOT, "profiles", tname)):
+        with open(os.path.join(ROOT, "profiles", tname)) as fh:
             traffic = {k: v for k, v in json.load(fh).items() if not k.startswith("_")}
-    # MFMA-busy fraction and sustained shader clock per kernel from hardware counters, same condition
-    counters = {}
-    cpath = os.path.join(ROOT, "profiles", "mfma_util_%s.json" % shape.name.replace("-", "_"))
-    if os.path.exists(cpath) and variant == "stem":
-        with open(cpath) as fh:
+    if os.path.exists(os.path.join(ROOT, "profiles", cname)) and variant == "stem":
+        with open(os.path.join(ROOT, "profiles", cname)) as fh:
             counters = {k: v for k, v in json.load(fh).items() if not k.startswith("_")}
     gemms = {k: v for k, v in kernels.items() if k.startswith("gemm_")}
     dom = max(gemms, key=lambda k: gemms[k]["avg_ms"] * gemms[k]["launches"])
     all_gemm_ms = sum(v["avg_ms"] for v in gemms.values())
     n_gemm_units = 6 if variant == "stem" else 9   # products of 2*T*d*F FLOP each per step
+    all_tf = n_gemm_units * gemm_flop / (all_gemm_ms * 1e-3) / 1e12
     roofline = {
         "bound": "mfma" if bf16 else "alu",
         "kernel": dom,
@@ -195,10 +312,13 @@ def main() -> int:
         "peak": peak_tf,
         "unit": "TFLOP/s",
         "frac": round(gemms[dom]["tflops"] / peak_tf, 4),
+        "frac_of_measured": round(gemms[dom]["tflops"] / peaks["mfma_bf16_tflops"], 4) if bf16 else None,
         "traffic": traffic.get(dom),
         "counters": counters.get(dom),
-        "all_gemms_tflops": round(n_gemm_units * gemm_flop / (all_gemm_ms * 1e-3) / 1e12, 2),
-        "all_gemms_frac": round(n_gemm_units * gemm_flop / (all_gemm_ms * 1e-3) / 1e12 / peak_tf, 4),
+        "traffic_and_counters_source": "profiles/%s, profiles/%s (committed rocprofv3 summaries of this command)" % (tname, cname),
+        "all_gemms_tflops": round(all_tf, 2),
+        "all_gemms_frac": round(all_tf / peak_tf, 4),
+        "all_gemms_frac_of_measured": round(all_tf / peaks["mfma_bf16_tflops"], 4) if bf16 else None,
     }
 
     out = {
@@ -207,8 +327,8 @@ def main() -> int:
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -217,16 +337,53 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T,
                    "n_uniq": U, "ids": "Zipf(s=1.1)", "variant": variant,
-                   "step": "fwd+bwd" if variant == "dense" else "fwd+bwd+embed_grad+sparse_adamw"},
+                   "step": "fwd+bwd" if variant == "dense" else "fwd+bwd+embed_grad+sparse_adamw",
+                   "sort_on_second_stream": bool(overlap_sort)},
+        # `value` is the whole step; the metric's own words (forward + backward) are here, both from HIP events
+        "step_ms": step_dist,
+        "fwd_bwd_ms": fb_dist,
+        "fwd_bwd_tokens_per_s": round(T / (fb_dist["median"] * 1e-3), 1),
+        "step_tokens_per_s_median": round(T / (step_dist["median"] * 1e-3), 1),
+        "measured_peak": peaks,
         "roofline": roofline,
         "kernels": kernels,
     }
-
-    if not args.no_cpu_baseline and variant == "stem":
-        out["cpu_baseline"] = cpu_baseline(shape, inp, args.cpu_sample_tokens, hp)
-    print(json.dumps(out))
     ctx.close()
-    return 0
+    return out, inp
+
+
+def secondary_runs(args, dev, peaks):
+    """Short runs of the other configurations, so that their figures come from the same command."""
+    import copy
+
+    import torch
+
+    from paper_2601_10639_amd import inputs
+    sec = {}
+    a = copy.copy(args)
+    a.variant, a.graph, a.cache_slots, a.calibrate_copy = "stem", False, 0, False
+    c2, _ = bench_layer(a, inputs.SHAPES["C2"], dev, 20, 5, peaks, detail=False)
+    sec["C2"] = {"workload": c2["config"]["workload"], "ms_per_step": c2["ms_per_step"], "tokens_per_s": c2["value"],
+                 "step_ms": c2["step_ms"], "fwd_bwd_ms": c2["fwd_bwd_ms"],
+                 "all_gemms_frac": c2["roofline"]["all_gemms_frac"],
+                 "table_grad_G3_frac_hbm": c2["kernels"].get("table_grad_G3", {}).get("frac_hbm_peak"),
+                 "sparse_adamw_frac_hbm": c2["kernels"].get("sparse_adamw", {}).get("frac_hbm_peak")}
+    del c2
+    torch.cuda.empty_cache()
+    a.steps, a.warmup = 50, 10
+    c4 = bench_decode(a, inputs.SHAPES["C4"], dev)
+    sec["C4"] = {"workload": c4["config"]["workload"], "us_per_step": c4["value"], "latency_ms": c4["latency_ms"],
+                 "frac_hbm_peak": c4["roofline"]["frac"], "layers": 16}
+    del c4
+    torch.cuda.empty_cache()
+    a.steps, a.warmup = 10, 3
+    c5 = bench_host_table(a, inputs.SHAPES["C5"], dev, ["zipf", "uniform"])
+    for kind, r in c5.items():
+        sec["C5_" + kind] = {"workload": r["config"]["workload"], "ms_per_step": r["ms_per_step"], "tokens_per_s": r["value"],
+                             "n_uniq": r["config"]["n_uniq"], "latency_ms": r["latency_ms"],
+                             "host_link_gbs": r["roofline"]["achieved"], "host_link_frac_of_contiguous_copy": r["roofline"]["frac"]}
+    torch.cuda.empty_cache()
+    return sec
 
 
 def _median_ms(fn, steps, warmup):
@@ -248,8 +405,8 @@ def _median_ms(fn, steps, warmup):
 
 def bench_decode(args, shape, dev):
     """One decode step: T single tokens through n_layers stacked layers (each with its own weights
-    and table), residual stream in bf16.  The residual add between layers is a torch op; the
-    layers are stem_ffn_forward calls.  HBM-bound on the weights: 2*d*F*2 bytes per layer."""
+    and table), residual stream in bf16.  Each layer is one stem_ffn_forward_residual call, in place
+    on the stream.  HBM-bound on the weights: 2*d*F*2 bytes per layer."""
     import torch
 
     from paper_2601_10639_amd import inputs, stemlib as L
@@ -269,9 +426,8 @@ def bench_decode(args, shape, dev):
 
     def step():
         x.copy_(x0)
-        for l in range(n_layers):
-            L.stem_ffn_forward(ctx, x, ids, Wg[l], Wd[l], E[l], y)
-            x.add_(y)
+        for l in range(n_layers):   # x <- x + layer_l(x): the add is part of the down product's epilogue
+            L.stem_ffn_forward_residual(ctx, x, ids, Wg[l], Wd[l], E[l], x, x)
 
     eager_step = step
     if args.graph:
@@ -313,7 +469,7 @@ def bench_decode(args, shape, dev):
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "layers": n_layers,
-                   "n_uniq": U, "ids": "Zipf(s=1.1)", "step": "16 x (forward + residual add)", "hip_graph": bool(args.graph)},
+                   "n_uniq": U, "ids": "Zipf(s=1.1)", "step": "16 x forward with the residual add fused (stem_ffn_forward_residual)", "hip_graph": bool(args.graph)},
         "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4),
                        "back_to_back": round(ms, 4), "kernels_only": round(kern_ms, 4)},
         "roofline": {"bound": "hbm", "kernel": "decode step (all kernels)",
@@ -322,40 +478,54 @@ def bench_decode(args, shape, dev):
                      "bytes": {"weights": weight_bytes, "table_rows": row_bytes, "activations": act_bytes}},
         "kernels": kernels,
     }
-    print(json.dumps(out))
     ctx.close()
-    return 0
+    return out
 
 
-def bench_host_table(args, shape, dev):
+def bench_host_table(args, shape, dev, id_kinds):
     """Forward of one layer over a long sequence with the table in pinned host memory: de-duplicate
     the ids, copy the distinct rows over the host link on a side stream while the gate GEMM runs,
     then the gather epilogue and the down GEMM.  Also times the same forward with a device-resident
-    table (what the copy exposes) and a plain pinned host-to-device copy (the link's rate)."""
+    table (what the copy exposes) and a plain pinned host-to-device copy (the link's rate).
+    One result per entry of id_kinds ("zipf", "uniform"), all on the same table and weights."""
+    import torch
+
+    from paper_2601_10639_amd import inputs
+
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    # drawn on the device and copied out: the host generator needs ten seconds for a billion draws
+    E_host = inputs.normal((V, F), 0.02, 53, torch.bfloat16, dev).cpu().pin_memory()
+    shared = {
+        "E_host": E_host,
+        "x": inputs.normal((T, d), 1.0, 54, torch.bfloat16, dev),
+        "Wg": inputs.normal((F, d), 0.02, 55, torch.bfloat16, dev),
+        "Wd": inputs.normal((d, F), 0.02, 56, torch.bfloat16, dev),
+        "E_dev": E_host.to(dev),
+    }
+    return {kind: _host_table_one(args, shape, dev, kind, shared) for kind in id_kinds}
+
+
+def _host_table_one(args, shape, dev, ids_kind, shared):
     import torch
 
     from paper_2601_10639_amd import inputs, stemlib as L
 
     T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
-    ids_np = inputs.zipf_ids(T, V, seed=51) if args.ids == "zipf" else inputs.uniform_ids(T, V, seed=52)
+    ids_np = inputs.zipf_ids(T, V, seed=51) if ids_kind == "zipf" else inputs.uniform_ids(T, V, seed=52)
     ids_host = torch.from_numpy(ids_np)
     U = len(set(ids_np.tolist()))
     ctx = L.stem_create(d, F, V, L.STEM_BF16, T, 0)
-    E_host = inputs.normal((V, F), 0.02, 53, torch.bfloat16, "cpu").pin_memory()
-    x = inputs.normal((T, d), 1.0, 54, torch.bfloat16, dev)
-    Wg = inputs.normal((F, d), 0.02, 55, torch.bfloat16, dev)
-    Wd = inputs.normal((d, F), 0.02, 56, torch.bfloat16, dev)
+    E_host, x, Wg, Wd, E_dev = (shared[k] for k in ("E_host", "x", "Wg", "Wd", "E_dev"))
     y = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
     E_compact = torch.empty(U + 8, F, dtype=torch.bfloat16, device=dev)
     remap = torch.empty(T, dtype=torch.int32, device=dev)
     ids_dev = ids_host.to(dev)
-    E_dev = E_host.to(dev)
     dedup_ms = []
     NS = args.cache_slots
     miss_rows, uniq_rows = [U], [U]
     if NS > 0:
         # one token stream: batches share the vocabulary (which ids are frequent) and differ in the draws
-        stream = [torch.from_numpy(inputs.zipf_ids(T, V, seed=500 + b, perm_seed=77) if args.ids == "zipf"
+        stream = [torch.from_numpy(inputs.zipf_ids(T, V, seed=500 + b, perm_seed=77) if ids_kind == "zipf"
                                    else inputs.uniform_ids(T, V, seed=500 + b))
                   for b in range(max(args.warmup, 10) + args.steps + 3)]   # no batch is seen twice
         E_cached = torch.empty(NS + T, F, dtype=torch.bfloat16, device=dev)
@@ -406,7 +576,7 @@ def bench_host_table(args, shape, dev):
         "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(med, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "n_uniq": uniq_rows[0],
-                   "ids": "Zipf(s=1.1)" if args.ids == "zipf" else "uniform",
+                   "ids": "Zipf(s=1.1)" if ids_kind == "zipf" else "uniform",
                    "cache_slots": NS, "rows_over_the_link": U,
                    "step": "dedup + row copy over the host link (side stream) + forward"},
         "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4),
@@ -418,9 +588,8 @@ def bench_host_table(args, shape, dev):
                      "bytes": nbytes, "peak_is": "measured contiguous pinned host-to-device copy of the same size"},
         "kernels": kernels,
     }
-    print(json.dumps(out))
     ctx.close()
-    return 0
+    return out
 
 
 def bench_host_training(args, shape, dev):

@@ -103,6 +103,16 @@ stem_status stem_ffn_forward(stem_ctx* ctx, const void* x, const int32_t* ids, c
                              const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y,
                              void* save_G, void* save_H, void* wait_event, void* stream);
 
+/* y = residual + layer(x): the forward pass with the layer's output added to a residual stream in the
+ * down product's own epilogue (sum in fp32, rounded once), as stacked layers are joined (the paper's
+ * model adds the FFN output to the residual stream; a decode step through many layers saves one
+ * element-wise kernel per layer this way).  residual [T,d], context dtype; y may be the same buffer as
+ * residual and as x (x is read completely before y is first written).  Inference form: no
+ * activations are saved, the table is device-resident.  Everything else as in stem_ffn_forward. */
+stem_status stem_ffn_forward_residual(stem_ctx* ctx, const void* x, const int32_t* ids, const void* W_gate,
+                                      const void* W_down, const void* E, int64_t E_rows, int64_t T,
+                                      const void* residual, void* y, void* stream);
+
 /* Backward of L = sum_i <y_i, dy_i> (chain rule of the layer equation; the paper
  * prints none).  dy [T,d]; saved_G [T,F] as written by forward (required); saved_H
  * [T,F] or NULL (then H is recomputed from saved_G and E).
@@ -130,6 +140,16 @@ stem_status stem_ffn_backward(stem_ctx* ctx, const void* dy, const void* x, cons
 stem_status stem_embed_grad(stem_ctx* ctx, const int32_t* ids, const void* dU, int64_t T,
                             int32_t* sorted_ids, int32_t* perm, int32_t* uniq_ids,
                             int32_t* seg_offsets, int32_t* n_uniq, float* dE_rows, void* stream);
+
+/* The floating-point half of stem_embed_grad alone, for a batch whose integer half is there
+ * already: a call of stem_embed_grad with dU == NULL and the same T on this context, which also
+ * leaves the run index of every sorted position in the context (until the next stem_embed_grad call).
+ * The integer half depends on the token ids only, so a caller can enqueue it early, on another
+ * stream, while the layer's products run, and call this one when dU exists; ordering the two calls
+ * (an event the second stream waits on) is the caller's business.  perm, seg_offsets: as written by
+ * that call.  dE_rows, dU: as in stem_embed_grad.  STEM_ERR_INVALID_ARG if T differs from that call's. */
+stem_status stem_embed_grad_presorted(stem_ctx* ctx, const void* dU, int64_t T, const int32_t* perm,
+                                      const int32_t* seg_offsets, float* dE_rows, void* stream);
 
 /* stem_embed_grad for callers that cannot allocate device memory: code under HIP graph capture,
  * serving loops and harnesses that forbid hipMalloc.  It needs no context: the scratch that
@@ -274,6 +294,18 @@ stem_status stem_profile_enable(stem_ctx* ctx, int on);
 int stem_profile_kernels(void);
 stem_status stem_profile_read(stem_ctx* ctx, int k, const char** name, double* total_ms, int64_t* launches);
 stem_status stem_profile_reset(stem_ctx* ctx);
+
+/* What this GPU sustains on the two resources the layer's kernels are priced against (the roofline
+ * denominators stay the published peaks; these say how much of them is reachable on the box at hand).
+ *   STEM_PEAK_MFMA_BF16: a loop of independent 32x32x16 bf16 MFMAs on register operands; *result in TFLOP/s.
+ *                        buf_a: at least 4096 bytes of device memory (practically never written).
+ *   STEM_PEAK_HBM_READ:  streaming read of buf_a [bytes]; *result in GB/s of bytes read.
+ *   STEM_PEAK_HBM_COPY:  streaming copy buf_a -> buf_b [bytes each]; *result in GB/s of bytes read plus written.
+ * Runs the kernel once untimed and `repeats` times between HIP events on `stream`, waits for each, and
+ * reports the best run.  Works on the current device; needs no context.  result: host. */
+typedef enum { STEM_PEAK_MFMA_BF16 = 0, STEM_PEAK_HBM_READ = 1, STEM_PEAK_HBM_COPY = 2 } stem_peak_kind;
+stem_status stem_measure_peak(int what, void* buf_a, void* buf_b, int64_t bytes, int repeats, void* stream,
+                              double* result);
 
 #ifdef __cplusplus
 }

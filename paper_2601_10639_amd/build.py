@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstem.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_skinny_bf16.hip", "kernels_f32.hip", "embed_grad.hip", "embed_grad_static.hip", "adamw.hip", "prefetch.hip", "edit.hip"]
+SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_skinny_bf16.hip", "kernels_f32.hip", "embed_grad.hip", "embed_grad_static.hip", "adamw.hip", "prefetch.hip", "edit.hip", "calibrate.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -192,6 +192,7 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
     return STEM_ERR_HIP;
   }
   memset(c->slot, 0xff, (size_t)desc->vocab * 4);
+  c->seg_T = -1;
   *c->flag = 0;
   c->err[0] = 0;
   *out = c;
@@ -211,16 +212,16 @@ stem_status stem_sync_status(stem_ctx* c, void* stream) {
   return STEM_OK;
 }
 
-stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, const void* W_gate,
-                             const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y,
-                             void* save_G, void* save_H, void* wait_event, void* stream) {
+static stem_status forward_impl(stem_ctx* c, const void* x, const int32_t* ids, const void* W_gate,
+                                const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y,
+                                void* save_G, void* save_H, void* wait_event, const void* residual, void* stream) {
   stem_status st = enter(c, T);
   if (st != STEM_OK) return st;
   if (T == 0) return STEM_OK;
   if (!x || !ids || !W_gate || !W_down || !E || !y)
     return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_forward: null pointer argument");
   if (misaligned(x) || misaligned(W_gate) || misaligned(W_down) || misaligned(E) || misaligned(y) ||
-      misaligned(save_G) || misaligned(save_H) || (reinterpret_cast<uintptr_t>(ids) & 3u))
+      misaligned(save_G) || misaligned(save_H) || misaligned(residual) || (reinterpret_cast<uintptr_t>(ids) & 3u))
     return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_forward: pointers must be 16-byte aligned");
   if (E_rows < 1 || E_rows > INT32_MAX) return fail(c, STEM_ERR_SHAPE, "stem_ffn_forward: E_rows = %lld", (long long)E_rows);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -240,6 +241,8 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
     b.A = static_cast<const bf16_t*>(H); b.lda = F;
     b.B = static_cast<const bf16_t*>(W_down); b.ldb = F;
     b.M = (int)T; b.N = d; b.K = F; b.C = y; b.flag = c->flag;
+    b.residual = static_cast<const bf16_t*>(residual);
+    const int down_epi = residual ? EPI_BF16_RES : EPI_BF16;
     if (!wait_event) {
       a.outG = static_cast<bf16_t*>(save_G); a.outH = static_cast<bf16_t*>(H);
       if (few) HIP_TRY(c, stem_gemm_skinny_bf16(c, K_GEMM_GATE, EPI_GATE, a, s));
@@ -260,8 +263,9 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
           GemmArgs bk = b;
           bk.A = static_cast<const bf16_t*>(H) + t0 * F;
           bk.C = static_cast<bf16_t*>(y) + t0 * d;
+          if (residual) bk.residual = static_cast<const bf16_t*>(residual) + t0 * d;
           bk.M = (int)tn;
-          HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, EPI_BF16, bk, s));
+          HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, down_epi, bk, s));
         }
         return STEM_OK;
       }
@@ -274,7 +278,7 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
       if ((size_t)b.ksplit * b.M * b.N * 4 > STEM_SPLITK_WS_BYTES) b.ksplit = 1;
       HIP_TRY(c, stem_gemm_skinny_bf16(c, K_GEMM_DOWN, b.ksplit > 1 ? EPI_SPLITK : EPI_BF16, b, s));
     } else {
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, EPI_BF16, b, s));
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DOWN, OP_KC, OP_KC, down_epi, b, s));
     }
   } else {
     float* G = static_cast<float*>(save_G ? save_G : c->dG_ws);
@@ -282,10 +286,26 @@ stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, con
                           static_cast<const float*>(W_gate), d, 1, G, (int)T, F, d, 0, s));
     if (wait_event) HIP_TRY(c, hipStreamWaitEvent(s, static_cast<hipEvent_t>(wait_event), 0));
     HIP_TRY(c, stem_silu_gather(c, 0, G, ids, E, (int)E_rows, H, T, F, s));
+    // with a residual the product is added to it: y starts as a copy of the residual unless it is the same buffer
+    if (residual && residual != y)
+      HIP_TRY(c, hipMemcpyAsync(y, residual, (size_t)T * d * 4, hipMemcpyDeviceToDevice, s));
     HIP_TRY(c, stem_sgemm(c, K_GEMM_DOWN, static_cast<const float*>(H), F, 1, static_cast<const float*>(W_down), F,
-                          1, static_cast<float*>(y), (int)T, d, F, 0, s));
+                          1, static_cast<float*>(y), (int)T, d, F, residual ? 1 : 0, s));
   }
   return STEM_OK;
+}
+
+stem_status stem_ffn_forward(stem_ctx* c, const void* x, const int32_t* ids, const void* W_gate,
+                             const void* W_down, const void* E, int64_t E_rows, int64_t T, void* y,
+                             void* save_G, void* save_H, void* wait_event, void* stream) {
+  return forward_impl(c, x, ids, W_gate, W_down, E, E_rows, T, y, save_G, save_H, wait_event, nullptr, stream);
+}
+
+stem_status stem_ffn_forward_residual(stem_ctx* c, const void* x, const int32_t* ids, const void* W_gate,
+                                      const void* W_down, const void* E, int64_t E_rows, int64_t T,
+                                      const void* residual, void* y, void* stream) {
+  if (c && !residual) return fail(c, STEM_ERR_INVALID_ARG, "stem_ffn_forward_residual: null residual");
+  return forward_impl(c, x, ids, W_gate, W_down, E, E_rows, T, y, nullptr, nullptr, nullptr, residual, stream);
 }
 
 stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const int32_t* ids,
@@ -531,8 +551,26 @@ stem_status stem_embed_grad(stem_ctx* c, const int32_t* ids, const void* dU, int
     return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad: dU and dE_rows must be 16-byte aligned");
   const EmbedScratch ws = embed_scratch(c);
   HIP_TRY(c, stem_sort_unique(c, ws, ids, T, c->desc.vocab, sorted_ids, perm, uniq_ids, seg_offsets, n_uniq, s));
+  c->seg_T = T;
   if (dU)
     HIP_TRY(c, stem_seg_reduce(c, ws, c->desc.dtype == STEM_BF16, dU, perm, seg_offsets, T, c->desc.d_ff, dE_rows, s));
+  return STEM_OK;
+}
+
+stem_status stem_embed_grad_presorted(stem_ctx* c, const void* dU, int64_t T, const int32_t* perm,
+                                      const int32_t* seg_offsets, float* dE_rows, void* stream) {
+  stem_status st = enter(c, T);
+  if (st != STEM_OK) return st;
+  if (T == 0) return STEM_OK;
+  if (!dU || !perm || !seg_offsets || !dE_rows)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad_presorted: null pointer argument");
+  if (misaligned(dU) || misaligned(dE_rows))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad_presorted: dU and dE_rows must be 16-byte aligned");
+  if (T != c->seg_T)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_embed_grad_presorted: T = %lld, but the context's run index is that of a "
+                "stem_embed_grad call with T = %lld", (long long)T, (long long)c->seg_T);
+  HIP_TRY(c, stem_seg_reduce(c, embed_scratch(c), c->desc.dtype == STEM_BF16, dU, perm, seg_offsets, T, c->desc.d_ff,
+                             dE_rows, static_cast<hipStream_t>(stream)));
   return STEM_OK;
 }
 

@@ -289,54 +289,65 @@ __global__ __launch_bounds__(1024) void sort_unique_fused_kernel(const int32_t* 
     __syncthreads();
     cur ^= 1;
   }
-  // unpack (coalesced), head flags into the free buffer
-  uint32_t* aux = buf[cur ^ 1];
+  // Unpack and number the runs, position k = u * 1024 + tid throughout (coalesced in global memory,
+  // conflict-free in LDS; with 16 consecutive positions per thread instead, every LDS access of this
+  // part was a 16-way bank conflict and the part took 14 of the kernel's 47 us).
+  // A position's run index is the number of run heads at or before it, minus one: heads of earlier
+  // (sweep, wavefront) pairs from a scanned table of ballot counts, heads of earlier lanes from the ballot.
+  int* cnt = table;                     // [sweep * SORT_WAVES + wave], reused
+  uint64_t headmask[ITEMS];
+  int idv[ITEMS];
 #pragma unroll
   for (int u = 0; u < ITEMS; ++u) {
     const int k = tid + 1024 * u;
+    bool head = false;
+    idv[u] = 0;
     if (k < T) {
       const uint32_t key = buf[cur][k];
       const int id = (int)(key >> pos_bits);
+      idv[u] = id;
       sorted_ids[k] = id;
       perm[k] = (int)(key & pos_mask);
-      aux[k] = (k == 0 || id != (int)(buf[cur][k - 1] >> pos_bits)) ? 1u : 0u;
+      head = (k == 0) || id != (int)(buf[cur][k - 1] >> pos_bits);
     }
+    headmask[u] = __ballot(head);
+    if (lane == 0) cnt[u * SORT_WAVES + wave] = __popcll(headmask[u]);
   }
   __syncthreads();
-  // run numbering in key order: each thread owns ITEMS consecutive positions
-  const int b0 = tid * ITEMS;
-  int heads = 0;
+  {  // exclusive scan of the ITEMS * SORT_WAVES = 256 counts by the first four wavefronts
+    int v = 0, inc = 0;
+    if (tid < ITEMS * SORT_WAVES) {
+      v = cnt[tid];
+      inc = v;
 #pragma unroll
-  for (int u = 0; u < ITEMS; ++u) if (b0 + u < T) heads += (int)aux[b0 + u];
-  int inc = heads;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(inc, o);
-    if (lane >= o) inc += t;
-  }
-  if (lane == 63) wsum[wave] = inc;
-  __syncthreads();
-  if (tid == 0) {
-    int c = 0;
-    for (int w = 0; w < 16; ++w) { const int t = wsum[w]; wsum[w] = c; c += t; }
-    seg_offsets[c] = T;
-    *n_uniq = c;
-  }
-  __syncthreads();
-  int run = wsum[wave] + inc - heads;
-#pragma unroll
-  for (int u = 0; u < ITEMS; ++u) {
-    const int k = b0 + u;
-    if (k < T) {
-      if (aux[k]) { uniq_ids[run] = (int)(buf[cur][k] >> pos_bits); seg_offsets[run] = k; ++run; }
-      aux[k] = (uint32_t)(run - 1);
+      for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+      }
+      if (lane == 63) wsum[wave] = inc;
+    }
+    __syncthreads();
+    if (tid < ITEMS * SORT_WAVES) {
+      int before = 0;
+      for (int w = 0; w < wave; ++w) before += wsum[w];
+      cnt[tid] = before + inc - v;
+      if (tid == ITEMS * SORT_WAVES - 1) {
+        const int total = before + inc;
+        seg_offsets[total] = T;
+        *n_uniq = total;
+      }
     }
   }
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < ITEMS; ++u) {
     const int k = tid + 1024 * u;
-    if (k < T) seg_of[k] = (int)aux[k];
+    if (k < T) {
+      const bool head = (headmask[u] >> lane) & 1ull;
+      const int run = cnt[u * SORT_WAVES + wave] + __popcll(headmask[u] & below) + (head ? 0 : -1);
+      if (head) { uniq_ids[run] = idv[u]; seg_offsets[run] = k; }
+      seg_of[k] = run;
+    }
   }
 }
 
@@ -446,52 +457,71 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(const void* __restrict_
   flush(cur);
 }
 
-// The chunk in which a border-crossing run starts adds up that run's pieces in chunk order.
+// The chunk in which a border-crossing run starts adds up that run's pieces: workgroup = that chunk
+// and a slab of 64 * COLS columns; the run's pieces are cut into four consecutive stretches, one per
+// wavefront, each summed in chunk order, and the four sums are added in order.  (One fixed
+// association, so every run gives the same bits.  With one thread summing all of a run's pieces the
+// most frequent id's 69 pieces were a chain of five dependent rounds of loads.)
 template <int COLS>
 __global__ __launch_bounds__(256) void seg_combine_kernel(const int32_t* __restrict__ seg_of,
                                                           const int32_t* __restrict__ seg_offsets, int64_t T,
                                                           int F, float* __restrict__ dE_rows,
                                                           const float* __restrict__ part) {
+  __shared__ float red[3][64][COLS + 1];
   const int c = blockIdx.x;
   const int k0 = c * SEG_ROWS;
   const int64_t k1 = (int64_t)k0 + SEG_ROWS;
   if (k1 >= T) return;                                 // nothing after this chunk
-  const int j = seg_of[k1 - 1];
-  if (seg_of[k1] != j) return;                         // the last run ends with the chunk
-  const int first = seg_of[k0];
-  if (first == j && k0 > 0 && seg_of[k0 - 1] == j) return;  // the run began in an earlier chunk
-  const int col = (blockIdx.y * 256 + threadIdx.x) * COLS;
-  if (col >= F) return;
+  // the four run indices that decide whether this chunk has anything to do, requested together
+  const int j = seg_of[k1 - 1], after = seg_of[k1], first = seg_of[k0], before = k0 > 0 ? seg_of[k0 - 1] : -1;
+  if (after != j) return;                              // the last run ends with the chunk
+  if (first == j && before == j) return;               // the run began in an earlier chunk
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = (blockIdx.y * 64 + lane) * COLS;
+  const bool live = col < F;
   const int slot = (first == j) ? 0 : 1;
   const int hi = seg_offsets[j + 1];
-  const int ce = (hi - 1) / SEG_ROWS;
+  const int n = (hi - 1) / SEG_ROWS - c + 1;           // pieces: this chunk's, then slot 0 of the following chunks
+  const int q = (n + 3) >> 2;
+  const int p0 = wave * q, p1 = min(n, p0 + q);
   float acc[COLS];
-  {
-    const float* src = part + ((int64_t)c * 2 + slot) * F + col;
 #pragma unroll
-    for (int q = 0; q < COLS; ++q) acc[q] = src[q];
-  }
-  constexpr int UNR = 16;
-  for (int cb = c + 1; cb <= ce; cb += UNR) {
-    float data[UNR][COLS];
+  for (int x = 0; x < COLS; ++x) acc[x] = 0.f;
+  if (live) {
+    constexpr int UNR = 16;
+    for (int pb = p0; pb < p1; pb += UNR) {
+      float data[UNR][COLS];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      if (cb + u <= ce) {
-        const float* src = part + ((int64_t)(cb + u) * 2) * F + col;
+      for (int u = 0; u < UNR; ++u) {
+        if (pb + u < p1) {
+          const int pc = pb + u;
+          const float* src = part + ((int64_t)(c + pc) * 2 + (pc == 0 ? slot : 0)) * F + col;
 #pragma unroll
-        for (int q = 0; q < COLS; q += 4) {
-          const float4 v = *reinterpret_cast<const float4*>(src + q);
-          data[u][q] = v.x; data[u][q + 1] = v.y; data[u][q + 2] = v.z; data[u][q + 3] = v.w;
+          for (int x = 0; x < COLS; x += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(src + x);
+            data[u][x] = v.x; data[u][x + 1] = v.y; data[u][x + 2] = v.z; data[u][x + 3] = v.w;
+          }
         }
       }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u)
+        if (pb + u < p1)
+#pragma unroll
+          for (int x = 0; x < COLS; ++x) acc[x] += data[u][x];
     }
-#pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      if (cb + u <= ce)
-#pragma unroll
-        for (int q = 0; q < COLS; ++q) acc[q] += data[u][q];
   }
-  store_cols<COLS>(dE_rows + (int64_t)j * F + col, acc);
+  if (wave > 0) {
+#pragma unroll
+    for (int x = 0; x < COLS; ++x) red[wave - 1][lane][x] = acc[x];
+  }
+  __syncthreads();
+  if (wave == 0 && live) {
+    for (int w = 1; w < 4; ++w)
+      if (w * q < n)
+#pragma unroll
+        for (int x = 0; x < COLS; ++x) acc[x] += red[w - 1][lane][x];
+    store_cols<COLS>(dE_rows + (int64_t)j * F + col, acc);
+  }
 }
 
 int bits_for(int V) {
@@ -569,10 +599,10 @@ hipError_t stem_seg_reduce(stem_ctx* ctx, const EmbedScratch& ws, int is_bf16, c
   {
     ProfScope ps(ctx, K_SEG_COMBINE, s);
     if (is_bf16)
-      hipLaunchKernelGGL(seg_combine_kernel<8>, dim3(chunks, slabs), dim3(256), 0, s, ws.seg_of, seg_offsets, T,
+      hipLaunchKernelGGL(seg_combine_kernel<8>, dim3(chunks, (F + 511) / 512), dim3(256), 0, s, ws.seg_of, seg_offsets, T,
                          F, dE_rows, ws.seg_part);
     else
-      hipLaunchKernelGGL(seg_combine_kernel<4>, dim3(chunks, slabs), dim3(256), 0, s, ws.seg_of, seg_offsets, T,
+      hipLaunchKernelGGL(seg_combine_kernel<4>, dim3(chunks, (F + 255) / 256), dim3(256), 0, s, ws.seg_of, seg_offsets, T,
                          F, dE_rows, ws.seg_part);
   }
   return hipGetLastError();

@@ -580,6 +580,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   };
   rsrc_t r0, r1;   // EPI_BF16 / EPI_F32: C;  gate-like: G (may be absent), H;  dH-like: dU, dG
   if (EPI == EPI_BF16) r0 = r1 = out_rsrc(p.C, 2);
+  else if (EPI == EPI_BF16_RES) { r0 = out_rsrc(p.C, 2); r1 = out_rsrc(const_cast<bf16_t*>(p.residual), 2); }
   else if (EPI == EPI_F32) r0 = r1 = out_rsrc(p.C, 4);
   else if (GATE_LIKE) { r0 = out_rsrc(p.outG, 2); r1 = out_rsrc(p.outH, 2); }
   else { r0 = out_rsrc(p.outdU, 2); r1 = out_rsrc(p.outdG, 2); }
@@ -621,6 +622,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       const uint32_t o2 = ok ? o * 2u : OOB, o4 = ok ? o * 4u : OOB;
       if (EPI == EPI_BF16) {
         store16(r0, o2, pack8(c));
+      } else if (EPI == EPI_BF16_RES) {
+        float rz[8], sum[8];
+        unpack8(__builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r1, o2, 0, 0)), rz);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) sum[q] = c[q] + rz[q];
+        store16(r0, o2, pack8(sum));
       } else if (EPI == EPI_F32) {
         // the previous value is fetched only when it is to be added to: otherwise the load is out of range and reads zero
         const uint32_t ol = p.accumulate ? o4 : OOB;
@@ -716,6 +723,7 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
   if ((int64_t)a.M * a.N * (epi == EPI_F32 ? 4 : 2) > lim) return hipErrorInvalidValue;
   if (la == OP_KC && lb == OP_KC) {
     if (epi == EPI_BF16) return launch<OP_KC, OP_KC, EPI_BF16>(ctx, kid, a, s);
+    if (epi == EPI_BF16_RES) return launch<OP_KC, OP_KC, EPI_BF16_RES>(ctx, kid, a, s);
     if (epi == EPI_GATE) return launch<OP_KC, OP_KC, EPI_GATE>(ctx, kid, a, s);
     if (epi == EPI_DH) return launch<OP_KC, OP_KC, EPI_DH>(ctx, kid, a, s);
     if (epi == EPI_GATE_UP) return launch<OP_KC, OP_KC, EPI_GATE_UP>(ctx, kid, a, s);

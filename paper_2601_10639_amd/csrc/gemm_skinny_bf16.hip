@@ -232,7 +232,13 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p) {
     const float c[4] = {s[0], s[1], s[2], s[3]};
     const size_t o = (size_t)m * p.N + n;
     if (EPI == EPI_BF16) {
-      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + o) = pack4(c);
+      float cr[4] = {c[0], c[1], c[2], c[3]};
+      if (p.residual) {   // the layer's output joins the residual stream: added in fp32, rounded once
+        const uint2 rv = *reinterpret_cast<const uint2*>(p.residual + o);
+        cr[0] += __uint_as_float(rv.x << 16); cr[1] += __uint_as_float(rv.x & 0xffff0000u);
+        cr[2] += __uint_as_float(rv.y << 16); cr[3] += __uint_as_float(rv.y & 0xffff0000u);
+      }
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + o) = pack4(cr);
     } else if (EPI == EPI_SPLITK) {
       *reinterpret_cast<f32x4_t*>(p.ws + ((size_t)z * p.M + m) * p.N + n) = s;
     } else {  // EPI_GATE
@@ -247,9 +253,9 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p) {
   }
 }
 
-// out[i] = bf16(sum over the k slices, in slice order, of ws[z][i]); 4 elements per thread
+// out[i] = bf16(sum over the k slices, in slice order, of ws[z][i] (+ residual[i])); 4 elements per thread
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ ws, int ksplit, int64_t total,
-                                                            bf16_t* __restrict__ out) {
+                                                            const bf16_t* residual, bf16_t* out) {
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= total) return;
   f32x4_t s = *reinterpret_cast<const f32x4_t*>(ws + i);
@@ -257,7 +263,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     const f32x4_t w = *reinterpret_cast<const f32x4_t*>(ws + (size_t)z * total + i);
     s += w;
   }
-  const float c[4] = {s[0], s[1], s[2], s[3]};
+  float c[4] = {s[0], s[1], s[2], s[3]};
+  if (residual) {   // may be the same buffer as out: every thread reads its four elements before it writes them
+    const uint2 rv = *reinterpret_cast<const uint2*>(residual + i);
+    c[0] += __uint_as_float(rv.x << 16); c[1] += __uint_as_float(rv.x & 0xffff0000u);
+    c[2] += __uint_as_float(rv.y << 16); c[3] += __uint_as_float(rv.y & 0xffff0000u);
+  }
   *reinterpret_cast<uint2*>(out + i) = pack4(c);
 }
 
@@ -294,7 +305,7 @@ hipError_t stem_gemm_skinny_bf16(stem_ctx* ctx, int kid, int epi, const GemmArgs
     const int64_t total = (int64_t)a.M * a.N;
     ProfScope ps(ctx, K_SPLITK_REDUCE, s);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s, p.ws,
-                       p.ksplit, total, static_cast<bf16_t*>(p.C));
+                       p.ksplit, total, p.residual, static_cast<bf16_t*>(p.C));
     return hipGetLastError();
   }
   p.ksplit = 1;

@@ -60,6 +60,7 @@ struct stem_ctx {
   int32_t* sort_vals[2]; // [max_tokens]
   int32_t* sort_counts;  // [64 * waves]
   int32_t* seg_of;       // [max_tokens] index of the segment each sorted position is in
+  int64_t seg_T;         // T of the call that last wrote seg_of (-1 = none)
   float* seg_part;       // [chunks][2][F] partial sums of segments that cross chunk borders
   int32_t* flag;         // pinned host int, device-visible: sticky id-range flag
 
@@ -131,7 +132,8 @@ enum GemmEpilogue {
   EPI_SPLITK,   // few-row kernel only: fp32 partial products per k slice, summed into bf16 C
   // dense SwiGLU (UP) and the additive variant (UPE): SiLU(C) is multiplied by Up or Up + E[ids]
   EPI_GATE_UP, EPI_GATE_UPE,
-  EPI_DH_UP, EPI_DH_UPE
+  EPI_DH_UP, EPI_DH_UPE,
+  EPI_BF16_RES  // C + residual -> bf16 [M,N] (decode chains: the layer's output joins the residual stream)
 };
 
 struct GemmArgs {
@@ -141,6 +143,7 @@ struct GemmArgs {
   int K_mc;        // k-rows that exist in a rows-contiguous operand (0 = K); the rest read as zero
   int lda, ldb;    // leading dimensions of the stored operands
   void* C;         // EPI_BF16 / EPI_F32 output, ld = N
+  const bf16_t* residual;  // EPI_BF16_RES (and the few-row kernel when not null): [M,N] bf16 added in fp32 before rounding
   int accumulate;  // EPI_F32: add to C
   const int32_t* ids;
   const bf16_t* E;

@@ -21,11 +21,11 @@ STEM_F32, STEM_BF16 = 0, 1
 
 SYMBOLS = [
     "stem_create", "stem_destroy", "stem_last_error", "stem_status_string", "stem_sync_status",
-    "stem_ffn_forward", "stem_ffn_backward", "stem_ffn_up_forward", "stem_ffn_up_backward",
-    "stem_embed_grad", "stem_embed_grad_noalloc", "stem_embed_sparse_adamw",
+    "stem_ffn_forward", "stem_ffn_forward_residual", "stem_ffn_backward", "stem_ffn_up_forward", "stem_ffn_up_backward",
+    "stem_embed_grad", "stem_embed_grad_presorted", "stem_embed_grad_noalloc", "stem_embed_sparse_adamw",
     "stem_prefetch_rows", "stem_cache_init", "stem_prefetch_rows_cached", "stem_cache_state",
     "stem_edit_rows", "stem_profile_enable", "stem_profile_kernels", "stem_profile_read",
-    "stem_profile_reset",
+    "stem_profile_reset", "stem_measure_peak",
 ]
 
 
@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.stem_sync_status.restype = i32
         L.stem_ffn_forward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp]
         L.stem_ffn_forward.restype = i32
+        L.stem_ffn_forward_residual.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        L.stem_ffn_forward_residual.restype = i32
         L.stem_ffn_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp, i32, vp]
         L.stem_ffn_backward.restype = i32
         L.stem_ffn_up_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp]
@@ -77,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.stem_ffn_up_backward.restype = i32
         L.stem_embed_grad.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
         L.stem_embed_grad.restype = i32
+        L.stem_embed_grad_presorted.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+        L.stem_embed_grad_presorted.restype = i32
         L.stem_embed_grad_noalloc.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         L.stem_embed_grad_noalloc.restype = i32
         L.stem_embed_sparse_adamw.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp,
@@ -103,6 +107,8 @@ def lib() -> ctypes.CDLL:
         L.stem_profile_read.restype = i32
         L.stem_profile_reset.argtypes = [vp]
         L.stem_profile_reset.restype = i32
+        L.stem_measure_peak.argtypes = [i32, vp, vp, i64, i32, vp, ctypes.POINTER(ctypes.c_double)]
+        L.stem_measure_peak.restype = i32
         _lib = L
     return _lib
 
@@ -194,6 +200,18 @@ def stem_ffn_forward(ctx: StemCtx, x, ids, W_gate, W_down, E, y, save_G=None, sa
     _check(ctx, st, "stem_ffn_forward")
 
 
+def stem_ffn_forward_residual(ctx: StemCtx, x, ids, W_gate, W_down, E, residual, y, stream=None, E_rows=None, T=None):
+    """y = residual + layer(x); y may be residual (and x) itself."""
+    dt = ctx.torch_dtype
+    T = x.shape[0] if T is None else T
+    E_rows = E.shape[0] if E_rows is None else E_rows
+    st = lib().stem_ffn_forward_residual(ctx.handle, _ptr(x, dt, name="x"), _ptr(ids, torch.int32, name="ids"),
+                                         _ptr(W_gate, dt, name="W_gate"), _ptr(W_down, dt, name="W_down"),
+                                         _ptr(E, dt, name="E"), E_rows, T, _ptr(residual, dt, name="residual"),
+                                         _ptr(y, dt, name="y"), _stream(stream))
+    _check(ctx, st, "stem_ffn_forward_residual")
+
+
 def stem_ffn_backward(ctx: StemCtx, dy, x, ids, W_gate, W_down, E, saved_G, saved_H, dx, dW_gate, dW_down, dU,
                       accumulate: bool = False, stream=None, E_rows=None, T=None):
     dt = ctx.torch_dtype
@@ -250,6 +268,16 @@ def stem_embed_grad(ctx: StemCtx, ids, dU, sorted_ids, perm, uniq_ids, seg_offse
                                _ptr(n_uniq, i32, name="n_uniq"), _ptr(dE_rows, torch.float32, name="dE_rows"),
                                _stream(stream))
     _check(ctx, st, "stem_embed_grad")
+
+
+def stem_embed_grad_presorted(ctx: StemCtx, dU, perm, seg_offsets, dE_rows, stream=None, T=None):
+    """The row sums alone, after a stem_embed_grad(dU=None) call on the same context and T."""
+    T = dU.shape[0] if T is None else T
+    st = lib().stem_embed_grad_presorted(ctx.handle, _ptr(dU, ctx.torch_dtype, name="dU"), T,
+                                         _ptr(perm, torch.int32, name="perm"),
+                                         _ptr(seg_offsets, torch.int32, name="seg_offsets"),
+                                         _ptr(dE_rows, torch.float32, name="dE_rows"), _stream(stream))
+    _check(ctx, st, "stem_embed_grad_presorted")
 
 
 def stem_embed_grad_noalloc(dtype: int, vocab: int, d_ff: int, ids, dU, sorted_ids, perm, uniq_ids, seg_offsets,
@@ -360,3 +388,16 @@ def stem_profile_read(ctx: StemCtx) -> dict:
         if n.value:
             out[name.value.decode()] = (ms.value, n.value)
     return out
+
+
+STEM_PEAK_MFMA_BF16, STEM_PEAK_HBM_READ, STEM_PEAK_HBM_COPY = 0, 1, 2
+
+
+def stem_measure_peak(what: int, buf_a, buf_b=None, repeats: int = 3, stream=None) -> float:
+    """TFLOP/s (MFMA loop) or GB/s (streaming read of buf_a / copy buf_a -> buf_b) this GPU sustains."""
+    out = ctypes.c_double(0.0)
+    nbytes = buf_a.numel() * buf_a.element_size()
+    st = lib().stem_measure_peak(what, _ptr(buf_a, name="buf_a"), _ptr(buf_b, name="buf_b"), nbytes, repeats,
+                                 _stream(stream), ctypes.byref(out))
+    _check(None, st, "stem_measure_peak")
+    return out.value

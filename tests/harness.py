@@ -52,7 +52,7 @@ def hip_forward_backward(ctx, inp, save_H=True, want_dx=True):
     return {"y": y, "G": G, "H": H, "dx": dx, "dW_gate": dWg, "dW_down": dWd, "dU": dU}
 
 
-def hip_embed_grad(ctx, ids, dU, V, with_rows=True):
+def hip_embed_grad(ctx, ids, dU, V, with_rows=True, stream=None):
     dev = ids.device
     T = ids.shape[0]
     cap = max(1, min(T, V))
@@ -66,7 +66,7 @@ def hip_embed_grad(ctx, ids, dU, V, with_rows=True):
     F = ctx.d_ff
     out["dE_rows"] = torch.empty(cap, F, dtype=torch.float32, device=dev) if with_rows else None
     L.stem_embed_grad(ctx, ids, dU if with_rows else None, out["sorted_ids"], out["perm"], out["uniq_ids"],
-                      out["seg_offsets"], out["n_uniq"], out["dE_rows"], T=T)
+                      out["seg_offsets"], out["n_uniq"], out["dE_rows"], T=T, stream=stream)
     return out
 
 

@@ -350,6 +350,62 @@ def test_edge_cases_and_error_reporting():
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype,T,d,F", [("bf16", 300, 128, 1024), ("bf16", 256, 192, 320), ("bf16", 700, 192, 576),
+                                         ("f32", 100, 72, 132)])
+def test_forward_with_residual_out_of_place_and_in_place(dtype, T, d, F):
+    """y = residual + layer(x), the sum taken in the down product's epilogue: the few-row kernel with and
+    without a K split (T = 300, 256), the 256x256-tile kernel (T = 700), the fp32 path; with a separate
+    residual and output, and in place on the layer's own input (a residual stream)."""
+    s = inputs.StemShape("residual", d, F, 500, 1, T, dtype)
+    inp = inputs.layer_inputs(s, seed=18, device=DEV, tokens=T)
+    dt = inp["x"].dtype
+    ctx = Hn.make_ctx(s, T)
+    f64 = {k: inputs.to_f64(v) for k, v in inp.items() if k != "ids"}
+    ids = inp["ids"].cpu().numpy()
+    layer, _ = O.ffn_forward(f64["x"], ids, f64["W_gate"], f64["W_down"], f64["E"])
+    # a residual of the layer output's own magnitude, so that neither term can hide an error in the other
+    res = inputs.normal((T, d), float(np.abs(layer).max()), 19, dt, DEV)
+    y = torch.empty(T, d, dtype=dt, device=DEV)
+    L.stem_ffn_forward_residual(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], res, y)
+    L.stem_sync_status(ctx)
+    assert Hn.max_rel(y.float().cpu(), inputs.to_f64(res) + layer) <= Hn.TOL[dtype]
+    assert Hn.max_rel(y.float().cpu().numpy().astype(np.float64) - inputs.to_f64(res), layer) <= 4 * Hn.TOL[dtype]
+    xs = inp["x"].clone()
+    L.stem_ffn_forward_residual(ctx, xs, inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], xs, xs)
+    L.stem_sync_status(ctx)
+    assert Hn.max_rel(xs.float().cpu(), f64["x"] + layer) <= Hn.TOL[dtype]
+    with pytest.raises(L.StemError) as e:
+        L.stem_ffn_forward_residual(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], None, y)
+    assert e.value.status == L.STEM_ERR_INVALID_ARG
+    ctx.close()
+
+
+def test_table_gradient_in_two_halves_on_two_streams():
+    """The integer half of the table gradient on a second stream, the row sums later on the main one
+    (stem_embed_grad with dU = NULL, then stem_embed_grad_presorted): same bits as the single call."""
+    T, V, F = 5000, 3000, 320
+    s = inputs.StemShape("two-halves", 64, F, V, 1, T, "bf16")
+    ctx = Hn.make_ctx(s, T)
+    ids_np = inputs.zipf_ids(T, V, seed=20)
+    ids = torch.from_numpy(ids_np).to(DEV)
+    dU = inputs.normal((T, F), 1.0, 21, torch.bfloat16, DEV)
+    want = Hn.hip_embed_grad(ctx, ids, dU, V)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    got = Hn.hip_embed_grad(ctx, ids, None, V, with_rows=False, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    rows = torch.full((min(T, V), F), 7.0, dtype=torch.float32, device=DEV)
+    L.stem_embed_grad_presorted(ctx, dU, got["perm"], got["seg_offsets"], rows)
+    L.stem_sync_status(ctx)
+    U = Hn.check_integers(got, ids_np)
+    assert torch.equal(rows[:U], want["dE_rows"][:U]) and bool((rows[U:] == 7.0).all())
+    with pytest.raises(L.StemError) as e:      # the context's run index belongs to a call with T tokens
+        L.stem_embed_grad_presorted(ctx, dU[:100], got["perm"], got["seg_offsets"], rows)
+    assert e.value.status == L.STEM_ERR_INVALID_ARG
+    ctx.close()
+
+
 def _expect_id_range(ctx):
     with pytest.raises(L.StemError) as e:
         L.stem_sync_status(ctx)

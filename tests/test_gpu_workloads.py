@@ -94,7 +94,8 @@ def test_c3_1b_shaped_layer_full_size():
     _full_size_case("C3", seed=22)
 
 
-def test_c4_decode_chain_sixteen_layers():
+@pytest.mark.parametrize("fused", [False, True])
+def test_c4_decode_chain_sixteen_layers(fused):
     """256 single tokens through 16 stacked 1B-shaped layers, residual stream rounded to bf16 between
     layers on both sides; every layer has its own weights and table, the ids are the same."""
     shape = inputs.SHAPES["C4"]
@@ -113,8 +114,11 @@ def test_c4_decode_chain_sixteen_layers():
         Wg = inputs.normal((F, d), 0.02, 100 + 3 * l, torch.bfloat16, DEV)
         Wd = inputs.normal((d, F), 0.02, 101 + 3 * l, torch.bfloat16, DEV)
         E = inputs.normal((V, F), 0.02, 102 + 3 * l, torch.bfloat16, DEV)
-        L.stem_ffn_forward(ctx, x, ids, Wg, Wd, E, y)
-        x = (x.float() + y.float()).to(torch.bfloat16)
+        if fused:   # the residual add in the down product's epilogue, in place on the stream
+            L.stem_ffn_forward_residual(ctx, x, ids, Wg, Wd, E, x, x)
+        else:
+            L.stem_ffn_forward(ctx, x, ids, Wg, Wd, E, y)
+            x = (x.float() + y.float()).to(torch.bfloat16)
         outs.append(x.float().cpu().numpy().astype(np.float64))
         layers_ref.append((inputs.to_f64(Wg), inputs.to_f64(Wd), inputs.to_f64(E[ui])))
         del E
