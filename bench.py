@@ -38,6 +38,8 @@ def main() -> int:
     ap.add_argument("--ids", default="zipf", choices=["zipf", "uniform"], help="id distribution for C5")
     ap.add_argument("--cache-slots", type=int, default=0,
                     help="C5: device-resident LFU cache of this many rows (0 = none); ten batches warm it first")
+    ap.add_argument("--prefetch-mode", default="kernel", choices=["kernel", "memcpy"],
+                    help="C5: how the distinct rows cross the host link (copy kernel reading pinned memory, or packed hipMemcpyAsync)")
     ap.add_argument("--graph", action="store_true", help="C4: capture the 16-layer step in a HIP graph and replay it")
     ap.add_argument("--host-state", action="store_true",
                     help="C2/C3: training step with the table, its fp32 master and the AdamW moments in pinned host "
@@ -149,7 +151,8 @@ def bench_layer(args, shape, dev, steps, warmup, peaks, detail):
     dt = inputs.torch_dtype(shape.dtype)
 
     inp = inputs.layer_inputs(shape, seed=3, device=dev)
-    ctx = L.stem_create(d, F, V, L.STEM_BF16 if bf16 else L.STEM_F32, T, 0)
+    ctx = L.stem_create(d, F, V, L.STEM_BF16 if bf16 else L.STEM_F32, T, 0,
+                        reserve=L.STEM_RESERVE_UP if args.variant != "stem" else 0)
     E = inp["E"]
     master = E.float() if bf16 else None
     m = torch.zeros(V, F, dtype=torch.float32, device=dev)
@@ -515,6 +518,8 @@ def _host_table_one(args, shape, dev, ids_kind, shared):
     ids_host = torch.from_numpy(ids_np)
     U = len(set(ids_np.tolist()))
     ctx = L.stem_create(d, F, V, L.STEM_BF16, T, 0)
+    if getattr(args, "prefetch_mode", "kernel") == "memcpy":
+        L.stem_set_prefetch_mode(ctx, L.STEM_PREFETCH_MEMCPY)
     E_host, x, Wg, Wd, E_dev = (shared[k] for k in ("E_host", "x", "Wg", "Wd", "E_dev"))
     y = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
     E_compact = torch.empty(U + 8, F, dtype=torch.bfloat16, device=dev)
@@ -577,7 +582,7 @@ def _host_table_one(args, shape, dev, ids_kind, shared):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": shape.name, "d_model": d, "d_ff": F, "vocab": V, "tokens": T, "n_uniq": uniq_rows[0],
                    "ids": "Zipf(s=1.1)" if ids_kind == "zipf" else "uniform",
-                   "cache_slots": NS, "rows_over_the_link": U,
+                   "cache_slots": NS, "rows_over_the_link": U, "prefetch_mode": getattr(args, "prefetch_mode", "kernel"),
                    "step": "dedup + row copy over the host link (side stream) + forward"},
         "latency_ms": {"median": round(med, 4), "p10": round(p10, 4), "p90": round(p90, 4),
                        "device_resident_forward": round(res_med, 4), "exposed_by_host_table": round(med - res_med, 4),

@@ -31,7 +31,9 @@
  *     valid ids are unaffected.
  *   - The context owns only scratch memory (sort buffers, partial sums, the
  *     internal H and dG buffers, pinned staging, one side stream and its events),
- *     all sized by stem_create from max_tokens; no call allocates.
+ *     all sized from max_tokens.  Memory is allocated by the set-up calls only:
+ *     stem_create, stem_reserve, stem_set_prefetch_mode, stem_cache_init,
+ *     stem_profile_enable.  No call that enqueues work allocates or frees.
  *     Calls on one context must not overlap in time (they share that scratch).
  */
 #ifndef STEM_H
@@ -76,6 +78,15 @@ typedef struct {
 /* Creates a context on HIP device `device` with scratch for calls of up to max_tokens
  * tokens.  *out is NULL on failure.  host pointers: out, desc. */
 stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max_tokens, int device);
+/* Scratch that only some entry points need, allocated on request (a set-up call: it allocates,
+ * enqueues nothing).  what: a sum of
+ *   STEM_RESERVE_UP    one more [max_tokens, d_ff] activation and one more [d_ff, d_model] weight buffer,
+ *                      for stem_ffn_up_forward / stem_ffn_up_backward (bf16 contexts);
+ *   STEM_RESERVE_EDIT  index lists and 64 replacement rows for stem_edit_rows.
+ * Those entry points return STEM_ERR_WORKSPACE until their scratch has been reserved. */
+#define STEM_RESERVE_UP 1u
+#define STEM_RESERVE_EDIT 2u
+stem_status stem_reserve(stem_ctx* ctx, uint32_t what);
 /* Synchronises the device and frees the context's scratch.  NULL is allowed. */
 void stem_destroy(stem_ctx* ctx);
 /* Text of the last error on this context (or of the last failed stem_create when
@@ -199,8 +210,8 @@ stem_status stem_embed_sparse_adamw(stem_ctx* ctx, const int32_t* uniq_ids, cons
 /* y = (SiLU(x W_gate^T) * (x W_up^T + E[ids])) W_down^T;  with E == NULL (ids unused) the
  * dense SwiGLU FFN y = (SiLU(x W_gate^T) * (x W_up^T)) W_down^T.  W_up [F,d]; everything else
  * as in stem_ffn_forward.  save_G, save_Up, save_H: [T,F] bf16 or NULL; backward needs all
- * three.  STEM_BF16 contexts only (STEM_ERR_UNSUPPORTED otherwise).  The first call on a
- * context allocates one more [max_tokens,F] activation and one more [F,d] weight buffer. */
+ * three.  STEM_BF16 contexts only (STEM_ERR_UNSUPPORTED otherwise); needs
+ * stem_reserve(ctx, STEM_RESERVE_UP). */
 stem_status stem_ffn_up_forward(stem_ctx* ctx, const void* x, const int32_t* ids, const void* W_gate,
                                 const void* W_up, const void* W_down, const void* E, int64_t E_rows,
                                 int64_t T, void* y, void* save_G, void* save_Up, void* save_H, void* stream);
@@ -234,6 +245,18 @@ stem_status stem_ffn_up_backward(stem_ctx* ctx, const void* dy, const void* x, c
 stem_status stem_prefetch_rows(stem_ctx* ctx, const void* E_host, const int32_t* ids_host, int64_t T,
                                void* E_compact, int64_t cap, int32_t* remap, int64_t* n_uniq_host,
                                int32_t* uniq_ids_host, void** ready_event);
+
+/* How stem_prefetch_rows moves the rows (a set-up call; the default is STEM_PREFETCH_KERNEL).
+ *   STEM_PREFETCH_KERNEL  a copy kernel on the side stream reads the pinned table directly, row by row in
+ *                         order of first use; the call blocks only for the host-side de-duplication.
+ *   STEM_PREFETCH_MEMCPY  the form the paper's system section describes: the distinct rows are packed into
+ *                         pinned staging by host threads and sent with hipMemcpyAsync, 32 MiB at a time,
+ *                         packing one piece while the previous one is on the link.  The call then blocks
+ *                         until the last piece has been packed (it waits on the copies of earlier pieces),
+ *                         and the forward call waits for the whole copy, not chunk by chunk.  Switching to
+ *                         it allocates the 64 MiB of staging. */
+typedef enum { STEM_PREFETCH_KERNEL = 0, STEM_PREFETCH_MEMCPY = 1 } stem_prefetch_mode;
+stem_status stem_set_prefetch_mode(stem_ctx* ctx, int mode);
 
 /* Host-resident table with a cache of the most frequently used rows on the device (System
  * Implementation: LFU cache of hot rows, only misses are prefetched).
@@ -277,7 +300,7 @@ typedef enum {
  * targets may overlap (a swap is two one-to-one calls' worth in one).  backup (device,
  * [n_s,F], may be NULL) receives the old source rows; writing them back undoes the edit.
  * src_ids, tgt_ids: host memory, at most 64 tokens each.  The mean is taken in fp32 and
- * rounded to the table's dtype.  When n_s < n_t the caller chooses which target tokens to
+ * rounded to the table's dtype.  Needs stem_reserve(ctx, STEM_RESERVE_EDIT).  When n_s < n_t the caller chooses which target tokens to
  * keep (the paper selects them by hand) and passes that subset.  Waits for `stream` once
  * (the index upload is synchronous); the row kernels run on `stream`.  Applies to one
  * table: call it for every STEM layer's table to edit a model. */
@@ -287,7 +310,7 @@ stem_status stem_edit_rows(stem_ctx* ctx, void* E, const int32_t* src_ids, int64
 /* ---- measurement aid ------------------------------------------------------------ */
 
 /* With profiling on, every kernel launch of the context is bracketed by HIP events on
- * the launch stream.  stem_profile_read synchronises the device, adds the elapsed time
+ * the launch stream (the first stem_profile_enable(ctx, 1) creates the events: a set-up call).  stem_profile_read synchronises the device, adds the elapsed time
  * of every recorded launch to per-kernel totals, and returns kernel `k`'s name, total
  * milliseconds and launch count (k in [0, stem_profile_kernels())).  Reset clears totals. */
 stem_status stem_profile_enable(stem_ctx* ctx, int on);

@@ -139,6 +139,16 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
   if (desc->d_model % mult || desc->d_ff % mult)
     return fail(nullptr, STEM_ERR_UNSUPPORTED, "stem_create: d_model=%d and d_ff=%d must be multiples of %d",
                 desc->d_model, desc->d_ff, mult);
+  // The bf16 kernels address every operand and output of a product through 32-bit buffer offsets:
+  // activations [max_tokens, d_ff], weights and fp32 weight gradients [d_ff, d_model] must each stay
+  // below 2 GiB.  (The table is addressed with 64-bit pointers and has no such limit.)
+  const int64_t lim = 0x7fffffff;
+  if (desc->dtype == STEM_BF16 &&
+      ((int64_t)max_tokens * std::max(desc->d_ff, desc->d_model) * 2 > lim || (int64_t)desc->d_ff * desc->d_model * 4 > lim))
+    return fail(nullptr, STEM_ERR_SHAPE,
+                "stem_create: max_tokens * max(d_ff, d_model) * 2 bytes = %lld and d_ff * d_model * 4 bytes = %lld must each "
+                "stay below 2^31 (32-bit buffer offsets); split the batch",
+                (long long)max_tokens * std::max(desc->d_ff, desc->d_model) * 2, (long long)desc->d_ff * desc->d_model * 4);
   if ((int64_t)max_tokens * desc->d_ff >= (1ll << 40))
     return fail(nullptr, STEM_ERR_SHAPE, "stem_create: max_tokens * d_ff too large");
   HIP_TRY(nullptr, hipSetDevice(device));
@@ -200,6 +210,37 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
 }
 
 void stem_destroy(stem_ctx* ctx) { release(ctx); }
+
+stem_status stem_reserve(stem_ctx* c, uint32_t what) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  if (what & ~(uint32_t)(STEM_RESERVE_UP | STEM_RESERVE_EDIT))
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_reserve: unknown bits in 0x%x", what);
+  HIP_TRY(c, hipSetDevice(c->device));
+  if ((what & STEM_RESERVE_UP) && !c->Up_ws) {
+    if (c->desc.dtype != STEM_BF16) return fail(c, STEM_ERR_UNSUPPORTED, "stem_reserve: STEM_RESERVE_UP needs a bf16 context");
+    HIP_TRY(c, hipMalloc(&c->Up_ws, std::max<size_t>((size_t)c->max_tokens * c->desc.d_ff * 2, 16)));
+    HIP_TRY(c, hipMalloc(&c->WT2_ws, (size_t)c->desc.d_ff * c->desc.d_model * 2));
+  }
+  if ((what & STEM_RESERVE_EDIT) && !c->edit_idx_dev) {
+    HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&c->edit_idx_dev), 3 * STEM_EDIT_MAX_TOKENS * sizeof(int32_t)));
+    HIP_TRY(c, hipMalloc(&c->edit_rep_dev, (size_t)STEM_EDIT_MAX_TOKENS * c->desc.d_ff * esize(c)));
+  }
+  return STEM_OK;
+}
+
+stem_status stem_set_prefetch_mode(stem_ctx* c, int mode) {
+  if (!c) return STEM_ERR_INVALID_ARG;
+  if (mode != STEM_PREFETCH_KERNEL && mode != STEM_PREFETCH_MEMCPY)
+    return fail(c, STEM_ERR_INVALID_ARG, "stem_set_prefetch_mode: unknown mode %d", mode);
+  if (mode == STEM_PREFETCH_MEMCPY && !c->pack_pinned) {
+    const size_t row_bytes = (size_t)c->desc.d_ff * esize(c);
+    HIP_TRY(c, hipSetDevice(c->device));
+    c->pack_bytes = std::max<size_t>((size_t)64 << 20, 2 * row_bytes);
+    HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pack_pinned), c->pack_bytes, hipHostMallocDefault));
+  }
+  c->prefetch_mode = mode;
+  return STEM_OK;
+}
 
 stem_status stem_sync_status(stem_ctx* c, void* stream) {
   if (!c) return STEM_ERR_INVALID_ARG;
@@ -401,13 +442,10 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
 // ---- dense SwiGLU FFN and the additive variant through the same kernels ---------------------------
 
 static stem_status up_scratch(stem_ctx* c) {
-  // these two entry points need one more [max_tokens, F] activation and one more transposed weight;
-  // they are allocated when the first such call arrives, not for every context
-  if (!c->Up_ws) {
-    HIP_TRY(c, hipSetDevice(c->device));
-    HIP_TRY(c, hipMalloc(&c->Up_ws, std::max<size_t>((size_t)c->max_tokens * c->desc.d_ff * 2, 16)));
-    HIP_TRY(c, hipMalloc(&c->WT2_ws, (size_t)c->desc.d_ff * c->desc.d_model * 2));
-  }
+  // these two entry points need one more [max_tokens, F] activation and one more transposed weight,
+  // which stem_reserve(ctx, STEM_RESERVE_UP) allocates
+  if (!c->Up_ws)
+    return fail(c, STEM_ERR_WORKSPACE, "the dense and additive variants need stem_reserve(ctx, STEM_RESERVE_UP) first");
   return STEM_OK;
 }
 
@@ -674,14 +712,9 @@ stem_status stem_prefetch_rows(stem_ctx* c, const void* E_host, const int32_t* i
                 (long long)U, (long long)cap);
 
   if (T > 0) HIP_TRY(c, hipMemcpyAsync(remap, c->remap_pinned, (size_t)T * 4, hipMemcpyHostToDevice, c->side));
-  const char* mode = getenv("STEM_PREFETCH_MODE");
-  if (mode && strcmp(mode, "memcpy") == 0) {
+  if (c->prefetch_mode == STEM_PREFETCH_MEMCPY) {
     // Pack the rows into pinned staging with a few host threads and copy chunk by chunk,
-    // packing chunk i+1 while chunk i is on the link.
-    if (!c->pack_pinned) {
-      c->pack_bytes = std::max<size_t>((size_t)64 << 20, 2 * row_bytes);
-      HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pack_pinned), c->pack_bytes, hipHostMallocDefault));
-    }
+    // packing chunk i+1 while chunk i is on the link (staging allocated by stem_set_prefetch_mode).
     const size_t half = c->pack_bytes / 2;
     const int64_t rows_per = (int64_t)(half / row_bytes);
     const unsigned hw = std::thread::hardware_concurrency();
@@ -943,10 +976,8 @@ stem_status stem_edit_rows(stem_ctx* c, void* E, const int32_t* src_ids_host, in
   }
   HIP_TRY(c, hipSetDevice(c->device));
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!c->edit_idx_dev) {
-    HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&c->edit_idx_dev), sizeof(idx)));
-    HIP_TRY(c, hipMalloc(&c->edit_rep_dev, (size_t)STEM_EDIT_MAX_TOKENS * c->desc.d_ff * esize(c)));
-  }
+  if (!c->edit_idx_dev)
+    return fail(c, STEM_ERR_WORKSPACE, "stem_edit_rows needs stem_reserve(ctx, STEM_RESERVE_EDIT) first");
   // the index lists are small and this call is rare: a synchronous upload keeps the host array on the stack
   HIP_TRY(c, hipStreamSynchronize(s));
   HIP_TRY(c, hipMemcpy(c->edit_idx_dev, idx, sizeof(idx), hipMemcpyHostToDevice));

@@ -77,6 +77,7 @@ struct stem_ctx {
   int pf_chunks;         // 0 = the last prefetch recorded no per-chunk events
   int64_t pf_T, pf_chunk_tokens;
   hipEvent_t pf_ev[STEM_PF_MAX_CHUNKS];
+  int prefetch_mode;     // STEM_PREFETCH_KERNEL or STEM_PREFETCH_MEMCPY
   char* pack_pinned;     // pinned host staging for the memcpy mode
   size_t pack_bytes;
   hipEvent_t pack_done[2];

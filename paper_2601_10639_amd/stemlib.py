@@ -20,7 +20,7 @@ STEM_ERR_INVALID_ARG, STEM_ERR_SHAPE, STEM_ERR_ID_RANGE, STEM_ERR_WORKSPACE, STE
 STEM_F32, STEM_BF16 = 0, 1
 
 SYMBOLS = [
-    "stem_create", "stem_destroy", "stem_last_error", "stem_status_string", "stem_sync_status",
+    "stem_create", "stem_reserve", "stem_set_prefetch_mode", "stem_destroy", "stem_last_error", "stem_status_string", "stem_sync_status",
     "stem_ffn_forward", "stem_ffn_forward_residual", "stem_ffn_backward", "stem_ffn_up_forward", "stem_ffn_up_backward",
     "stem_embed_grad", "stem_embed_grad_presorted", "stem_embed_grad_noalloc", "stem_embed_sparse_adamw",
     "stem_prefetch_rows", "stem_cache_init", "stem_prefetch_rows_cached", "stem_cache_state",
@@ -58,6 +58,10 @@ def lib() -> ctypes.CDLL:
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.stem_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(stem_layer_desc), i64, i32]
         L.stem_create.restype = i32
+        L.stem_reserve.argtypes = [vp, ctypes.c_uint32]
+        L.stem_reserve.restype = i32
+        L.stem_set_prefetch_mode.argtypes = [vp, i32]
+        L.stem_set_prefetch_mode.restype = i32
         L.stem_destroy.argtypes = [vp]
         L.stem_destroy.restype = None
         L.stem_last_error.argtypes = [vp]
@@ -171,12 +175,30 @@ def _ptr(t, dtype=None, cuda=True, name="tensor") -> ctypes.c_void_p:
     return ctypes.c_void_p(t.data_ptr())
 
 
-def stem_create(d_model: int, d_ff: int, vocab: int, dtype: int, max_tokens: int, device: int = 0) -> StemCtx:
+STEM_RESERVE_UP, STEM_RESERVE_EDIT = 1, 2
+STEM_NOALLOC_MAX_TOKENS = 65536
+STEM_PREFETCH_KERNEL, STEM_PREFETCH_MEMCPY = 0, 1
+
+
+def stem_create(d_model: int, d_ff: int, vocab: int, dtype: int, max_tokens: int, device: int = 0,
+                reserve: int = 0) -> StemCtx:
+    """reserve: a sum of STEM_RESERVE_* bits passed on to stem_reserve."""
     desc = stem_layer_desc(d_model, d_ff, vocab, dtype)
     out = ctypes.c_void_p(None)
     st = lib().stem_create(ctypes.byref(out), ctypes.byref(desc), max_tokens, device)
     _check(None, st, "stem_create")
-    return StemCtx(out.value, d_model, d_ff, vocab, dtype, max_tokens, device)
+    ctx = StemCtx(out.value, d_model, d_ff, vocab, dtype, max_tokens, device)
+    if reserve:
+        stem_reserve(ctx, reserve)
+    return ctx
+
+
+def stem_reserve(ctx: StemCtx, what: int):
+    _check(ctx, lib().stem_reserve(ctx.handle, what), "stem_reserve")
+
+
+def stem_set_prefetch_mode(ctx: StemCtx, mode: int):
+    _check(ctx, lib().stem_set_prefetch_mode(ctx.handle, mode), "stem_set_prefetch_mode")
 
 
 def stem_destroy(ctx: StemCtx):

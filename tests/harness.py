@@ -28,9 +28,9 @@ def max_rel(got, ref) -> float:
     return float(np.abs(got - ref).max() / den)
 
 
-def make_ctx(shape: inputs.StemShape, max_tokens: int) -> L.StemCtx:
+def make_ctx(shape: inputs.StemShape, max_tokens: int, reserve: int = 0) -> L.StemCtx:
     dt = L.STEM_BF16 if shape.dtype == "bf16" else L.STEM_F32
-    return L.stem_create(shape.d_model, shape.d_ff, shape.vocab, dt, max_tokens, 0)
+    return L.stem_create(shape.d_model, shape.d_ff, shape.vocab, dt, max_tokens, 0, reserve=reserve)
 
 
 def hip_forward_backward(ctx, inp, save_H=True, want_dx=True):

@@ -58,6 +58,11 @@ def test_create_rejects_bad_descriptors_on_the_host(lib):
     assert create(64, 64, 10, L.STEM_BF16, -1) == L.STEM_ERR_SHAPE          # negative capacity
     assert create(6, 8, 10, L.STEM_F32, 8) == L.STEM_ERR_UNSUPPORTED        # fp32 needs multiples of 4
     assert lib.stem_create(None, None, 8, 0) == L.STEM_ERR_INVALID_ARG
+    # bf16 activations of 2 GiB or more do not fit the kernels' 32-bit buffer offsets: refused with the limit named
+    assert create(2048, 8192, 128256, L.STEM_BF16, 131072) == L.STEM_ERR_SHAPE
+    assert b"2^31" in lib.stem_last_error(None)
+    assert create(8192, 2048, 1000, L.STEM_BF16, 131072) == L.STEM_ERR_SHAPE      # [T, d_model] is the large one here
+    assert create(32768, 32768, 10, L.STEM_BF16, 8) == L.STEM_ERR_SHAPE           # fp32 weight gradient of 4 GiB
 
 
 def test_null_context_is_refused(lib):
@@ -68,6 +73,15 @@ def test_null_context_is_refused(lib):
     assert lib.stem_embed_sparse_adamw(z, z, z, 1, z, z, z, z, z, None, z) == L.STEM_ERR_INVALID_ARG
     assert lib.stem_sync_status(z, z) == L.STEM_ERR_INVALID_ARG
     assert lib.stem_profile_enable(z, 1) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_reserve(z, 1) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_set_prefetch_mode(z, 0) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_ffn_forward_residual(z, z, z, z, z, z, 1, 1, z, z, z) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_embed_grad_presorted(z, z, 1, z, z, z, z) == L.STEM_ERR_INVALID_ARG
+    # the calls that need no context check their arguments on the host as well
+    assert lib.stem_embed_grad_noalloc(7, 10, 8, z, z, 1, z, z, z, z, z, z, z, z) == L.STEM_ERR_INVALID_ARG
+    assert lib.stem_embed_grad_noalloc(L.STEM_BF16, 10, 8, z, z, L.STEM_NOALLOC_MAX_TOKENS + 1, z, z, z, z, z, z, z, z) == L.STEM_ERR_SHAPE
+    assert b"65536" in lib.stem_last_error(None)
+    assert lib.stem_measure_peak(9, z, z, 4096, 1, z, None) == L.STEM_ERR_INVALID_ARG
     lib.stem_destroy(z)  # allowed
 
 

@@ -149,7 +149,7 @@ def test_bf16_dense_swiglu_and_additive_variant(T, d, F, with_table):
     Wu = inputs.normal((F, d), 0.02, 18, torch.bfloat16, DEV)
     E = inp["E"] if with_table else None
     ids = inp["ids"] if with_table else None
-    ctx = Hn.make_ctx(s, T)
+    ctx = Hn.make_ctx(s, T, reserve=L.STEM_RESERVE_UP)
     bf = torch.bfloat16
     y = torch.empty(T, d, dtype=bf, device=DEV)
     G, Up, H, dV = (torch.empty(T, F, dtype=bf, device=DEV) for _ in range(4))
@@ -267,7 +267,7 @@ def test_knowledge_edit_row_operations(dtype):
     V, F = 200, 320
     s = inputs.StemShape("edit", 64, F, V, 1, 8, dtype)
     dt = inputs.torch_dtype(dtype)
-    ctx = Hn.make_ctx(s, 8)
+    ctx = Hn.make_ctx(s, 8, reserve=L.STEM_RESERVE_EDIT)
     E0 = inputs.normal((V, F), 0.02, 51, dt, DEV)
     E64 = inputs.to_f64(E0)
     rnd = O.bf16_round if dtype == "bf16" else (lambda a: a.astype(np.float32).astype(np.float64))
@@ -343,6 +343,22 @@ def test_edge_cases_and_error_reporting():
         L.stem_sync_status(ctx)
     assert e.value.status == L.STEM_ERR_ID_RANGE
     L.stem_sync_status(ctx)  # flag was cleared
+    # scratch of the optional entry points is reserved explicitly; without it they refuse to run
+    cb = L.stem_create(64, 64, 100, L.STEM_BF16, 8, 0)
+    z16 = torch.zeros(8, 64, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(L.StemError) as e:
+        L.stem_ffn_up_forward(cb, z16, None, z16[:64].repeat(8, 1), z16[:64].repeat(8, 1), z16[:64].repeat(8, 1), None, z16.clone())
+    assert e.value.status == L.STEM_ERR_WORKSPACE and "STEM_RESERVE_UP" in str(e.value)
+    with pytest.raises(L.StemError) as e:
+        L.stem_edit_rows(cb, torch.zeros(100, 64, dtype=torch.bfloat16, device=DEV), [1], [2], L.STEM_EDIT_REPLACE)
+    assert e.value.status == L.STEM_ERR_WORKSPACE
+    with pytest.raises(L.StemError) as e:
+        L.stem_reserve(cb, 64)
+    assert e.value.status == L.STEM_ERR_INVALID_ARG
+    with pytest.raises(L.StemError) as e:
+        L.stem_set_prefetch_mode(cb, 5)
+    assert e.value.status == L.STEM_ERR_INVALID_ARG
+    cb.close()
     # unsupported widths are refused at creation
     with pytest.raises(L.StemError) as e:
         L.stem_create(100, 256, 10, L.STEM_BF16, 8, 0)

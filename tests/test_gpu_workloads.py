@@ -187,15 +187,9 @@ def _prefetch_case(shape, T, ids_np, seed, mode=None):
     E_compact = torch.full((cap, F), 7.0, dtype=dt, device=DEV)
     remap = torch.empty(T, dtype=torch.int32, device=DEV)
     uniq_host = torch.empty(cap, dtype=torch.int32)
-    old = os.environ.pop("STEM_PREFETCH_MODE", None)
-    if mode:
-        os.environ["STEM_PREFETCH_MODE"] = mode
-    try:
-        n, ev = L.stem_prefetch_rows(ctx, E_host, ids_host, E_compact, remap, uniq_host)
-    finally:
-        os.environ.pop("STEM_PREFETCH_MODE", None)
-        if old is not None:
-            os.environ["STEM_PREFETCH_MODE"] = old
+    if mode == "memcpy":
+        L.stem_set_prefetch_mode(ctx, L.STEM_PREFETCH_MEMCPY)
+    n, ev = L.stem_prefetch_rows(ctx, E_host, ids_host, E_compact, remap, uniq_host)
     assert n == len(o_uniq) and ev
     x = inputs.normal((T, d), 1.0, seed + 1, dt, DEV)
     Wg = inputs.normal((F, d), 0.02, seed + 2, dt, DEV)
