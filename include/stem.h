@@ -321,12 +321,18 @@ stem_status stem_profile_reset(stem_ctx* ctx);
 /* What this GPU sustains on the two resources the layer's kernels are priced against (the roofline
  * denominators stay the published peaks; these say how much of them is reachable on the box at hand).
  *   STEM_PEAK_MFMA_BF16: a loop of independent 32x32x16 bf16 MFMAs on register operands; *result in TFLOP/s.
- *                        buf_a: at least 4096 bytes of device memory (practically never written).
+ *                        buf_a: device memory (practically never written).
+ *   STEM_PEAK_MFMA_BF16_DATA: the same number of MFMAs per wavefront, arranged as the 4 x 4 outer product of
+ *                        fragments of a GEMM wave tile, on operands read from buf_a (its first 64 KiB, taken as
+ *                        bf16 values: fill it with the data of interest, e.g. unit normals); buf_b: 4 bytes or
+ *                        more (practically never written).  The rate depends on the data: the more operand bits
+ *                        toggle, the more power the matrix cores draw and the lower the clock the chip sustains.
  *   STEM_PEAK_HBM_READ:  streaming read of buf_a [bytes]; *result in GB/s of bytes read.
  *   STEM_PEAK_HBM_COPY:  streaming copy buf_a -> buf_b [bytes each]; *result in GB/s of bytes read plus written.
  * Runs the kernel once untimed and `repeats` times between HIP events on `stream`, waits for each, and
- * reports the best run.  Works on the current device; needs no context.  result: host. */
-typedef enum { STEM_PEAK_MFMA_BF16 = 0, STEM_PEAK_HBM_READ = 1, STEM_PEAK_HBM_COPY = 2 } stem_peak_kind;
+ * reports the best run.  Works on the current device; needs no context; bytes (the size of buf_a, and of buf_b for
+ * the copy) is a multiple of 16 and at least 65536.  result: host. */
+typedef enum { STEM_PEAK_MFMA_BF16 = 0, STEM_PEAK_HBM_READ = 1, STEM_PEAK_HBM_COPY = 2, STEM_PEAK_MFMA_BF16_DATA = 3 } stem_peak_kind;
 stem_status stem_measure_peak(int what, void* buf_a, void* buf_b, int64_t bytes, int repeats, void* stream,
                               double* result);
 

@@ -20,7 +20,7 @@ const char* const kKernelNames[K_COUNT_] = {
     "gemm_gate_fused", "gemm_gate_plain", "gemm_down",    "gemm_dh_fused", "gemm_dx",      "gemm_dw_down",
     "gemm_dw_gate",    "silu_gather",     "dh_epilogue",  "sort_count",    "sort_scan",    "sort_scatter",
     "sort_fused",      "unique",          "seg_reduce",   "seg_combine",   "sparse_adamw", "row_copy",
-    "transpose",       "splitk_reduce",   "gemm_up",      "gemm_dw_up"};
+    "splitk_reduce",   "gemm_up",      "gemm_dw_up"};
 
 #define fail stem_fail
 
@@ -63,8 +63,8 @@ void release(stem_ctx* c) {
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
   (void)hipFree(c->H_ws); (void)hipFree(c->dG_ws); (void)hipFree(c->dH_ws);
-  (void)hipFree(c->WT_ws); (void)hipFree(c->actT_ws); (void)hipFree(c->splitk_ws); (void)hipFree(c->dw_ws);
-  (void)hipFree(c->Up_ws); (void)hipFree(c->WT2_ws);
+  (void)hipFree(c->splitk_ws); (void)hipFree(c->dw_ws);
+  (void)hipFree(c->Up_ws);
   for (int i = 0; i < 2; ++i) { (void)hipFree(c->sort_keys[i]); (void)hipFree(c->sort_vals[i]); }
   (void)hipFree(c->sort_counts); (void)hipFree(c->seg_of); (void)hipFree(c->seg_part);
   (void)hipFree(c->uniq_dev);
@@ -166,8 +166,6 @@ stem_status stem_create(stem_ctx** out, const stem_layer_desc* desc, int64_t max
   ok(hipMalloc(&c->dG_ws, std::max<size_t>(TF * es, 16)));
   if (desc->dtype == STEM_F32) ok(hipMalloc(&c->dH_ws, std::max<size_t>(TF * 4, 16)));
   if (desc->dtype == STEM_BF16) {
-    ok(hipMalloc(&c->WT_ws, (size_t)desc->d_ff * desc->d_model * 2));
-    ok(hipMalloc(&c->actT_ws, std::max<size_t>((size_t)desc->d_model * ((max_tokens + 63) / 64 * 64) * 2, 16)));
     ok(hipMalloc(reinterpret_cast<void**>(&c->splitk_ws), STEM_SPLITK_WS_BYTES));
     // Weight gradients are [d,F] outputs with K = T: a narrow layer has fewer 256x256 tiles than the
     // chip has compute units, so its K range is cut into slices (at most 8, at most ~256 workgroups).
@@ -219,7 +217,6 @@ stem_status stem_reserve(stem_ctx* c, uint32_t what) {
   if ((what & STEM_RESERVE_UP) && !c->Up_ws) {
     if (c->desc.dtype != STEM_BF16) return fail(c, STEM_ERR_UNSUPPORTED, "stem_reserve: STEM_RESERVE_UP needs a bf16 context");
     HIP_TRY(c, hipMalloc(&c->Up_ws, std::max<size_t>((size_t)c->max_tokens * c->desc.d_ff * 2, 16)));
-    HIP_TRY(c, hipMalloc(&c->WT2_ws, (size_t)c->desc.d_ff * c->desc.d_model * 2));
   }
   if ((what & STEM_RESERVE_EDIT) && !c->edit_idx_dev) {
     HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&c->edit_idx_dev), 3 * STEM_EDIT_MAX_TOKENS * sizeof(int32_t)));
@@ -382,44 +379,38 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
     const bf16_t* dyb = static_cast<const bf16_t*>(dy);
     const bf16_t* Hb = static_cast<const bf16_t*>(H);
     bf16_t* dGb = static_cast<bf16_t*>(c->dG_ws);
-    bf16_t* WT = static_cast<bf16_t*>(c->WT_ws);
-    bf16_t* actT = static_cast<bf16_t*>(c->actT_ws);
-    const int ldT = (int)((T + 63) / 64 * 64);
     int dw_split = c->dw_ksplit;   // K slices of the weight-gradient GEMMs: at least 8 K tiles each
-    while (dw_split > 1 && ldT / 64 / dw_split < 8) dw_split /= 2;
-    // The weight operands of the two activation-gradient products are needed K-contiguous:
-    // transposing a [d,F] matrix costs a few percent of the product it feeds.
-    {  // dH = dy W_down, fused into dU and dG;  W_down^T is [F,d]
-      HIP_TRY(c, stem_transpose_bf16(c, W_down, d, F, WT, d, s));
+    while (dw_split > 1 && (T + 63) / 64 / dw_split < 8) dw_split /= 2;
+    // Every operand is read as it is stored.  The weights of the two activation-gradient products
+    // ([K, N] with N contiguous) and both operands of the weight-gradient products ([T, rows]) are
+    // rows-contiguous: their tiles go to LDS unchanged and the fragment reads transpose them.
+    {  // dH = dy W_down, fused into dU and dG
       GemmArgs a = {};
-      a.A = dyb; a.lda = d; a.B = WT; a.ldb = d;
+      a.A = dyb; a.lda = d; a.B = static_cast<const bf16_t*>(W_down); a.ldb = F;
       a.M = (int)T; a.N = F; a.K = d;
       a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows; a.flag = c->flag;
       a.inG = static_cast<const bf16_t*>(saved_G); a.outdU = static_cast<bf16_t*>(dU); a.outdG = dGb;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_KC, EPI_DH, a, s));
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_MC, EPI_DH, a, s));
     }
-    {  // dW_down[d,F] = dy^T H;  dy^T is [d, ldT] with zero padding along T
-      HIP_TRY(c, stem_transpose_bf16(c, dy, (int)T, d, actT, ldT, s));
+    {  // dW_down[d,F] = dy^T H
       GemmArgs a = {};
-      a.A = actT; a.lda = ldT; a.B = Hb; a.ldb = F;
-      a.M = d; a.N = F; a.K = ldT; a.K_mc = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
+      a.A = dyb; a.lda = d; a.B = Hb; a.ldb = F;
+      a.M = d; a.N = F; a.K = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
       a.ksplit = dw_split; a.ws = c->dw_ws;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_KC, OP_MC, EPI_F32, a, s));
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_MC, OP_MC, EPI_F32, a, s));
     }
-    if (dx) {  // dx = dG W_gate;  W_gate^T is [d,F]
-      HIP_TRY(c, stem_transpose_bf16(c, W_gate, F, d, WT, F, s));
+    if (dx) {  // dx = dG W_gate
       GemmArgs a = {};
-      a.A = dGb; a.lda = F; a.B = WT; a.ldb = F;
+      a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(W_gate); a.ldb = d;
       a.M = (int)T; a.N = d; a.K = F; a.C = dx; a.flag = c->flag;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_KC, EPI_BF16, a, s));
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_MC, EPI_BF16, a, s));
     }
-    {  // dW_gate[F,d] = dG^T x = (x^T dG)^T: computed as [F,d] with A = dG (rows-contiguous), B = x^T
-      HIP_TRY(c, stem_transpose_bf16(c, x, (int)T, d, actT, ldT, s));
+    {  // dW_gate[F,d] = dG^T x
       GemmArgs a = {};
-      a.A = dGb; a.lda = F; a.B = actT; a.ldb = ldT;
-      a.M = F; a.N = d; a.K = ldT; a.K_mc = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
+      a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(x); a.ldb = d;
+      a.M = F; a.N = d; a.K = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
       a.ksplit = dw_split; a.ws = c->dw_ws;
-      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_KC, EPI_F32, a, s));
+      HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_MC, EPI_F32, a, s));
     }
   } else {
     const float* dyf = static_cast<const float*>(dy);
@@ -442,8 +433,8 @@ stem_status stem_ffn_backward(stem_ctx* c, const void* dy, const void* x, const 
 // ---- dense SwiGLU FFN and the additive variant through the same kernels ---------------------------
 
 static stem_status up_scratch(stem_ctx* c) {
-  // these two entry points need one more [max_tokens, F] activation and one more transposed weight,
-  // which stem_reserve(ctx, STEM_RESERVE_UP) allocates
+  // these two entry points need one more [max_tokens, F] activation, which
+  // stem_reserve(ctx, STEM_RESERVE_UP) allocates
   if (!c->Up_ws)
     return fail(c, STEM_ERR_WORKSPACE, "the dense and additive variants need stem_reserve(ctx, STEM_RESERVE_UP) first");
   return STEM_OK;
@@ -523,48 +514,39 @@ stem_status stem_ffn_up_backward(stem_ctx* c, const void* dy, const void* x, con
   const bf16_t* dyb = static_cast<const bf16_t*>(dy);
   bf16_t* dGb = static_cast<bf16_t*>(c->dG_ws);
   bf16_t* dVb = static_cast<bf16_t*>(dV);
-  bf16_t* WT = static_cast<bf16_t*>(c->WT_ws);
-  bf16_t* WT2 = static_cast<bf16_t*>(c->WT2_ws);
-  bf16_t* actT = static_cast<bf16_t*>(c->actT_ws);
-  const int ldT = (int)((T + 63) / 64 * 64);
   int dw_split = c->dw_ksplit;
-  while (dw_split > 1 && ldT / 64 / dw_split < 8) dw_split /= 2;
+  while (dw_split > 1 && (T + 63) / 64 / dw_split < 8) dw_split /= 2;
   {  // dH = dy W_down, fused into dV = dH * SiLU(G) and dG = dH * (Up [+ E[ids]]) * SiLU'(G)
-    HIP_TRY(c, stem_transpose_bf16(c, W_down, d, F, WT, d, s));
     GemmArgs a = {};
-    a.A = dyb; a.lda = d; a.B = WT; a.ldb = d;
+    a.A = dyb; a.lda = d; a.B = static_cast<const bf16_t*>(W_down); a.ldb = F;
     a.M = (int)T; a.N = F; a.K = d;
     a.ids = ids; a.E = static_cast<const bf16_t*>(E); a.E_rows = (int)E_rows; a.flag = c->flag;
     a.inG = static_cast<const bf16_t*>(saved_G); a.inUp = static_cast<const bf16_t*>(saved_Up);
     a.outdU = dVb; a.outdG = dGb;
-    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_KC, E ? EPI_DH_UPE : EPI_DH_UP, a, s));
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DH, OP_KC, OP_MC, E ? EPI_DH_UPE : EPI_DH_UP, a, s));
   }
   {  // dW_down[d,F] = dy^T H
-    HIP_TRY(c, stem_transpose_bf16(c, dy, (int)T, d, actT, ldT, s));
     GemmArgs a = {};
-    a.A = actT; a.lda = ldT; a.B = static_cast<const bf16_t*>(saved_H); a.ldb = F;
-    a.M = d; a.N = F; a.K = ldT; a.K_mc = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
+    a.A = dyb; a.lda = d; a.B = static_cast<const bf16_t*>(saved_H); a.ldb = F;
+    a.M = d; a.N = F; a.K = (int)T; a.C = dW_down; a.accumulate = accumulate; a.flag = c->flag;
     a.ksplit = dw_split; a.ws = c->dw_ws;
-    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_KC, OP_MC, EPI_F32, a, s));
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWDOWN, OP_MC, OP_MC, EPI_F32, a, s));
   }
   if (dx) {  // dx = dG W_gate + dV W_up: one product over the concatenated K range
-    HIP_TRY(c, stem_transpose_bf16(c, W_gate, F, d, WT, F, s));
-    HIP_TRY(c, stem_transpose_bf16(c, W_up, F, d, WT2, F, s));
     GemmArgs a = {};
-    a.A = dGb; a.lda = F; a.B = WT; a.ldb = F;
-    a.A2 = dVb; a.B2 = WT2; a.K2 = F;
+    a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(W_gate); a.ldb = d;
+    a.A2 = dVb; a.B2 = static_cast<const bf16_t*>(W_up); a.K2 = F;
     a.M = (int)T; a.N = d; a.K = F; a.C = dx; a.flag = c->flag;
-    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_KC, EPI_BF16, a, s));
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DX, OP_KC, OP_MC, EPI_BF16, a, s));
   }
   {  // dW_gate[F,d] = dG^T x and dW_up[F,d] = dV^T x
-    HIP_TRY(c, stem_transpose_bf16(c, x, (int)T, d, actT, ldT, s));
     GemmArgs a = {};
-    a.A = dGb; a.lda = F; a.B = actT; a.ldb = ldT;
-    a.M = F; a.N = d; a.K = ldT; a.K_mc = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
+    a.A = dGb; a.lda = F; a.B = static_cast<const bf16_t*>(x); a.ldb = d;
+    a.M = F; a.N = d; a.K = (int)T; a.C = dW_gate; a.accumulate = accumulate; a.flag = c->flag;
     a.ksplit = dw_split; a.ws = c->dw_ws;
-    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_KC, EPI_F32, a, s));
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWGATE, OP_MC, OP_MC, EPI_F32, a, s));
     a.A = dVb; a.C = dW_up;
-    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWUP, OP_MC, OP_KC, EPI_F32, a, s));
+    HIP_TRY(c, stem_gemm_bf16(c, K_GEMM_DWUP, OP_MC, OP_MC, EPI_F32, a, s));
   }
   return STEM_OK;
 }

@@ -3,25 +3,28 @@
 //
 // One kernel template computes  C[m,n] = sum_k Aop[m,k] * Bop[n,k]  on a 256x256
 // output tile per workgroup: 4 wavefronts, each a 128x128 quadrant held as 4x4
-// accumulators of v_mfma_f32_32x32x16_bf16, K stepped by 64 through five 32 KB LDS
-// slots (one operand tile each), so that every global request is made more than a
+// accumulators of v_mfma_f32_32x32x16_bf16, K stepped by 64 through a ring of five 32 KB
+// LDS slots (one operand tile each), so that every global request is made more than a
 // whole K tile before its data is needed.
 //
-// Operands.  "KC" = stored [rows,K] with K contiguous: tiles go global -> LDS directly
-// (buffer_load ... lds, 16 bytes per lane, whole 128-byte lines per row; half lines were
-// measured to halve the L1 rate).  "MC" = stored [K,rows] with rows contiguous: tiles go
-// through registers, are transposed 8x8 there and written to LDS, so the MFMA loop always
-// reads 16-byte K-contiguous fragments from one LDS layout.  All loads are buffer loads:
-// out-of-range rows / k read as zero, so ragged edges need no branches.
+// Operands.  "KC" = stored [rows,K] with K contiguous, "MC" = stored [K,rows] with rows
+// contiguous.  Tiles of both kinds go global -> LDS directly (buffer_load ... lds, 16 bytes per
+// lane, whole 128-byte lines; half lines were measured to halve the L1 rate) and keep the
+// orientation they have in memory; what differs is the fragment read.  A KC tile gives an MFMA
+// fragment (8 consecutive k of one row) as one 16-byte LDS read; an MC tile gives it as two
+// ds_read_b64_tr_b16, the LDS read of gfx950 that transposes 16-bit values across 16 lanes.  So
+// no operand is ever transposed in memory or in registers: the backward products read the
+// weights, the activations and their gradients exactly as the forward pass left them.  (An
+// earlier version staged MC tiles through registers with byte permutes and needed the other
+// operand K-contiguous, i.e. four transposing kernels per backward pass; its weight-gradient
+// loops ran at 2800-3060 clocks per K tile against 2050-2300 for this one.)  All loads are
+// buffer loads: out-of-range rows / k read as zero, so ragged edges need no branches.
 //
-// LDS tile layout: row r (an m or n index within the tile) owns 128 bytes = 8 chunks of
+// LDS layout of a KC tile: row r (an m or n index within the tile) owns 128 bytes = 8 chunks of
 // 8 bf16; chunk c of row r sits at chunk slot (c ^ (r >> 1) ^ (((r >> 3) & 3) << 1)) & 7.  With
 // the first term a ds_read_b128 of one chunk column over 16 consecutive rows touches all 64
-// banks once; the second term spreads rows 8 and 16 apart, which the transposing stores of a
-// register-staged operand write together.  Measured per instruction with four wavefronts
-// issuing: fragment reads 16 clocks (conflict-free) with or without the second term, those stores
-// 64 clocks with it and 128 without; XORing the same two row bits into slot bits 0 and 1 instead
-// makes the stores as cheap but the reads conflict 2-way.
+// banks once (measured per instruction with four wavefronts issuing: 16 clocks, conflict-free).
+// The layout of an MC tile is described at its loader.
 //
 // Schedule.  One iteration = one K tile = 4 k-steps of 16 MFMAs.  Fragments are double
 // buffered in registers: while the MFMAs of k-step s run, the 8 fragment reads of step
@@ -30,7 +33,7 @@
 // which its MFMA queue drains, so they are never issued back to back).  The single
 // barrier per iteration sits before the last k-step, so that step overlaps the first
 // fragment reads of the next tile, and the wait before it leaves the youngest requests
-// in flight.  The loop is unrolled over the slot rotation (5 or 6 K tiles) so that every
+// in flight.  The loop is unrolled over the slot rotation (5 K tiles) so that every
 // LDS address is a loop-invariant register plus an immediate.
 //
 // Epilogue.  The MFMA is issued with the N-side fragment as its row operand, so a lane
@@ -78,8 +81,25 @@ struct Window {
     r = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, left < 0 ? 0 : left, 0x00020000);
   }
   __device__ __forceinline__ rsrc_t rsrc() const { return r; }
+  // the same descriptor as four words (base, stride 0, byte count, raw-buffer flags), for loads issued as assembly
+  __device__ __forceinline__ u32x4_t words() const {
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    return u32x4_t{(uint32_t)b, (uint32_t)(b >> 32) & 0xffffu, (uint32_t)(left < 0 ? 0 : left), 0x00020000u};
+  }
   __device__ __forceinline__ void advance(int bytes) { base += bytes; left -= bytes; rebuild(); }
 };
+
+// One direct-to-LDS load of 16 bytes per lane, written as assembly.  The compiler orders every
+// transposing LDS read (ds_read_b64_tr_b16) after ALL outstanding direct-to-LDS loads it knows of
+// (a wait for vmcnt(0) in front of each), which would drain the ring in every k-step; products
+// with a rows-contiguous operand therefore issue their loads where the compiler does not see
+// them.  Nothing returns to a register, and the kernel's own waits (vmcnt before each barrier) are
+// what orders these loads against the reads, as they do for the compiler-made ones.  M0 (the LDS
+// destination) is written inside the statement; the compiler never keeps a value of its own in M0
+// across other code (it sets it directly in front of each instruction that reads it).
+__device__ __forceinline__ void lds_dma_16(u32x4_t rs, uint32_t lds_dst, uint32_t off) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_dst), "v"(off), "s"(rs) : "memory");
+}
 
 // ---- KC operand: global -> LDS direct -----------------------------------------------
 // Wavefront w loads row groups g = w*8 + i (8 rows each); lane -> row g*8 + (lane >> 3),
@@ -102,56 +122,58 @@ struct LoaderKC {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(win.rsrc(), (lds_ptr_t)(tile + (wave * 8 + i) * 1024), 16, off[i], 0, 0,
                                              0);
   }
+  __device__ __forceinline__ void issue_opaque(int i, char* tile, int wave) const {
+    lds_dma_16(win.words(), lds_addr(tile + (wave * 8 + i) * 1024), off[i]);
+  }
   __device__ __forceinline__ void next_tile() { win.advance(BK * 2); }
 };
 
-// ---- MC operand: global -> registers -> 8x8 transpose -> LDS ---------------------------
-// Thread t owns the 8(k) x 8(rows) block kb = (t >> 3) & 7, rb = (t & 7) + 8 * (t >> 6) of the
-// 64 x 256 tile: eight consecutive lanes read the eight 16-byte pieces of one 128-byte line (with
-// consecutive lanes on different k rows instead, the same loads cost the products 5 % more time).
-// The price is a 4-way bank conflict on the transposed LDS stores, which LDS has room for.
+// ---- MC operand: global -> LDS as stored, transposed by the fragment reads ----------------
+// The 64 x 256 tile keeps the operand's own orientation in LDS: K row k owns 512 bytes = 32 chunks
+// of 8 rows-of-the-product (m or n), chunk c at chunk slot c ^ ((k & 3) << 2).  A wavefront's load
+// instruction fills 1 KB = two K rows; the lane fetches the chunk that belongs in its slot, so 32
+// lanes read one 512-byte stretch of a global row.  ds_read_b64_tr_b16 then delivers MFMA fragments:
+// within 16 lanes, lane 4a + b supplies the address of 4 consecutive 16-bit values of "row" a, piece
+// b, and lane j receives the j-th value of rows 0..3 (checked on the device with an index pattern).
+// With a = k and b = 4-column piece, lane j ends up with 4 consecutive k of column j: half a
+// fragment.  The slot swizzle puts the four K rows that 16 lanes read in different 64-byte bank
+// groups, so 32 lanes (one LDS pass of a 64-bit read) touch all 64 banks once.
 struct LoaderMC {
-  uint32_t off0;
-  uint32_t ld2;
+  uint32_t off[8];
+  uint32_t tile_bytes;   // one K tile further along the operand
   Window win;
-  uint32_t wbase[4];   // offset within a tile of this thread's rows rb*8 + 2j; row 2j+1 is 128 bytes on
-  uint4 st[2][8];   // two tiles' worth of loads may be in flight (the ring schedule); else only set 0
-  __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int K, int row0, int tid) {
+  __device__ __forceinline__ void init(const bf16_t* p, int ld, int rows, int K, int row0, int wave, int lane) {
     win.set(p, (int64_t)K * ld * 2);
-    ld2 = (uint32_t)ld * 2;
-    const int kb = (tid >> 3) & 7, rb = (tid & 7) + 8 * (tid >> 6);
-    off0 = (row0 + rb * 8) < rows ? (uint32_t)(((int64_t)kb * 8 * ld + row0 + rb * 8) * 2) : OOB;
+    tile_bytes = (uint32_t)ld * (BK * 2);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wbase[j] = lds_off(rb * 8 + 2 * j, kb);
-  }
-  __device__ __forceinline__ void issue(int kk, int set = 0) {
-    const uint32_t o = off0 == OOB ? OOB : off0 + kk * ld2;
-    st[set][kk] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(win.rsrc(), o, 0, 0));
-  }
-  __device__ __forceinline__ void next_tile() { win.advance((int)(BK * ld2)); }
-  static __device__ __forceinline__ uint32_t pick(const uint4& v, int q) {
-    return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
-  }
-  // rows r of this thread's block, transposed so that k runs along the 16-byte chunk, to the
-  // tile at LDS address `tile`.  The store is written as assembly on purpose: for a compiler-made
-  // LDS store the compiler first waits for every outstanding direct-to-LDS load (it cannot tell
-  // that those go to other slots), which would drain the other operand's requests in the middle
-  // of the K tile.  The callers order these stores themselves (lgkmcnt(0) and a barrier before
-  // any wavefront reads the tile).
-  __device__ __forceinline__ void commit(int r, uint32_t tile, int set = 0) const {
-    const int q = r >> 1;
-    u32x4_t w;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t lo = pick(st[set][2 * j], q), hi = pick(st[set][2 * j + 1], q);
-      // one byte permute: the two high (odd r) or the two low (even r) halves of hi:lo
-      w[j] = __builtin_amdgcn_perm(hi, lo, (r & 1) ? 0x07060302u : 0x05040100u);
+    for (int i = 0; i < 8; ++i) {
+      const int k = (wave * 8 + i) * 2 + (lane >> 5);
+      const int c = (lane & 31) ^ ((k & 3) << 2);
+      off[i] = (row0 + c * 8) < rows ? (uint32_t)(((int64_t)k * ld + row0 + c * 8) * 2) : OOB;
     }
-    const uint32_t a = tile + wbase[q];
-    if (r & 1) asm volatile("ds_write_b128 %0, %1 offset:128" ::"v"(a), "v"(w) : "memory");
-    else asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(w) : "memory");
+  }
+  __device__ __forceinline__ void issue(int i, char* tile, int wave) const {
+    lds_dma_16(win.words(), lds_addr(tile + (wave * 8 + i) * 1024), off[i]);
+  }
+  __device__ __forceinline__ void next_tile() { win.advance((int)tile_bytes); }
+  // Byte offset within a tile of this lane's address for the first half (k + 0..3) of fragment i
+  // (rows w*128 + i*32 .. +31 of the product) of k-step 0; the second half is 2048 bytes on, k-step
+  // s another s * 8192.  Lane = 16 g + 4 a + b: K row 8 (g >> 1) + a, rows 16 (g & 1) + 4 b .. + 3.
+  static __device__ __forceinline__ uint32_t frag_off(int w, int i, int lane) {
+    const int g = lane >> 4, a = (lane >> 2) & 3, b = lane & 3;
+    const int c = w * 16 + i * 4 + 2 * (g & 1) + (b >> 1);
+    return (uint32_t)((8 * (g >> 1) + a) * 512 + ((c ^ (a << 2)) << 4) + 8 * (b & 1));
   }
 };
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+// one MFMA fragment (8 consecutive k of this lane's row) from a tile in the layout above
+__device__ __forceinline__ bf16x8_t lds_read_frag_tr(const char* p) {
+  typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_ptr_t) const_cast<char*>(p));
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_ptr_t) const_cast<char*>(p + 2048));
+  return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
 
 // ---- epilogue math ------------------------------------------------------------------
 __device__ __forceinline__ float sigmoidf_fast(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
@@ -189,12 +211,6 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int ntm, int ntn, i
 
 template <int LA, int LB, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
-  // (KC,KC) products keep their operand tiles in a ring of five 32 KB slots (A and B tiles of
-  // successive K tiles in turn) instead of two 64 KB stages: see the main loop.
-  constexpr bool RING = (LA == OP_KC && LB == OP_KC);
-  // products with exactly one register-staged operand use the same five slots: see their main loop
-  constexpr bool RING_MC = ((LA == OP_KC) != (LB == OP_KC));
-  static_assert(RING || RING_MC, "at least one operand takes the direct path");
   __shared__ __attribute__((aligned(16))) char smem[5 * TILE_BYTES];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -212,14 +228,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     const int nk_all = (p.K + BK - 1) / BK;
     const int per = (nk_all + p.ksplit - 1) / p.ksplit;
     const int k0 = z * per * BK;
-    const int kmc = (p.K_mc > 0 ? p.K_mc : p.K) - k0;        // rows of a rows-contiguous operand left
     int klen = p.K - k0;
     if (klen > per * BK) klen = per * BK;
     if (klen < 0) klen = 0;
     p.A += LA == OP_KC ? (size_t)k0 : (size_t)k0 * p.lda;
     p.B += LB == OP_KC ? (size_t)k0 : (size_t)k0 * p.ldb;
     p.K = klen;
-    p.K_mc = kmc < 0 ? 0 : (kmc < klen ? kmc : klen);
     p.kc_skip = k0;                                          // K-contiguous windows end k0 elements earlier
     p.C = p.ws + (size_t)z * p.M * p.N;
     p.accumulate = 0;
@@ -234,11 +248,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   // weight-gradient products gained nothing from the same rotation, so they do not rotate).  The sum over k is the same set of products in
   // a rotated order.  `rot` is the first K element of this workgroup's loop; 0 = no rotation.
   int rot = 0;
-  if (RING && !p.A2) {
+  if (LA == OP_KC && LB == OP_KC && !p.A2) {
     const int nk_all = (p.K + BK - 1) / BK;
     if (nk_all >= 16) rot = (int)((long)(blockIdx.x & 7) * nk_all / 8) * BK;
   }
-  if (RING && rot > 0) {   // expressed as two operand pairs: [rot, K) of A, B and then [0, rot)
+  if (LA == OP_KC && LB == OP_KC && rot > 0) {   // expressed as two operand pairs: [rot, K) of A, B and then [0, rot)
     p.A2 = p.A; p.B2 = p.B; p.K2 = rot;
     p.A += rot; p.B += rot; p.K -= rot; p.kc_skip += rot;
   }
@@ -252,9 +266,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   LoaderKC ka, kb_;
-  LoaderMC ma, mb;
-  if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane, p.kc_skip); else ma.init(p.A, p.lda, p.M, p.K_mc > 0 ? p.K_mc : p.K, m0, tid);
-  if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane, p.kc_skip); else mb.init(p.B, p.ldb, p.N, p.K_mc > 0 ? p.K_mc : p.K, n0, tid);
+  LoaderMC da, db;
+  if (LA == OP_KC) ka.init(p.A, p.lda, p.M, m0, wave, lane, p.kc_skip); else da.init(p.A, p.lda, p.M, p.K, m0, wave, lane);
+  if (LB == OP_KC) kb_.init(p.B, p.ldb, p.N, n0, wave, lane, p.kc_skip); else db.init(p.B, p.ldb, p.N, p.K, n0, wave, lane);
 
   // fragments: lane -> row (lane & 31) of a 32-row block, k half (lane >> 5) of a k-step; within a k-step
   // they are read in the order a0,b0,b1,a1,b2,b3,a2,a3
@@ -270,10 +284,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     }
   };
 
-  // A second operand pair (A2, B2, K2; both K-contiguous, same leading dimensions) continues the
-  // sum: after the K tiles of the first pair the windows move to the second.
+  // A second operand pair (A2, B2, K2; same layouts and leading dimensions as the first; A
+  // K-contiguous) continues the sum: after the K tiles of the first pair the windows move to the second.
   const int nk1 = (p.K + BK - 1) / BK;
-  const int nk = nk1 + ((LA == OP_KC && LB == OP_KC && p.A2) ? (p.K2 + BK - 1) / BK : 0);
+  const int nk = nk1 + ((LA == OP_KC && p.A2) ? (p.K2 + BK - 1) / BK : 0);
   // The gate epilogue reads one gathered table row per output row.  A few K tiles before the end
   // of the main loop each lane touches the 128-byte lines its wavefront will need, so that they
   // travel from HBM to L2 under the MFMA work instead of in a burst when all workgroups reach
@@ -320,116 +334,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   };
   const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
   bf16x8_t xa[4], xb[4], ya[4], yb[4];
-  if constexpr (RING_MC) {
-  // ---- one direct and one register-staged operand: five 32 KB slots ---------------------------
-  // The register-staged operand's K tile t lives in slot t & 1, the direct operand's in slot
-  // 2 + t % 3.  While K tile t is multiplied: the staged loads of tile t+2 are requested during
-  // its first k-step (into the register set that tile t's own data left), the direct loads of
-  // tile t+2 during the next two k-steps (into the slot tile t-1 left), and in the last k-step
-  // before the barrier the registers holding tile t+1 are transposed into LDS.  Every request has
-  // more than a whole K tile's time before it is waited for, and two tiles' requests stay in
-  // flight across the barrier.
-  constexpr bool A_DIRECT = (LA == OP_KC);
-  LoaderKC& kd = *(A_DIRECT ? &ka : &kb_);
-  LoaderMC& mr = *(A_DIRECT ? &mb : &ma);
-  const int wr = A_DIRECT ? wn : wm, wd = A_DIRECT ? wm : wn;
-  uint32_t rr_addr[4], rd_addr[2][4];   // staged: slot 1 is an immediate away; direct: [slot pair][k-step]
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ lds_swz(frow)) & 7) << 4);
-    rr_addr[ks] = (uint32_t)((wr * 128 + frow) * 128) + sw;
-#pragma unroll
-    for (int pr = 0; pr < 2; ++pr) rd_addr[pr][ks] = (uint32_t)((2 + 2 * pr) * TILE_BYTES + (wd * 128 + frow) * 128) + sw;
-  }
-  // fragment q of k-step ks of a K tile with index t6 modulo 6
-  auto rfrag_mc = [&](int t6, int ks, int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
-    constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
-    constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
-    const int sr = t6 & 1, sd = t6 % 3;
-    const bool direct = (isA[q] != 0) == A_DIRECT;
-    const char* src = direct ? smem + rd_addr[sd >> 1][ks] + (sd & 1) * TILE_BYTES + idx[q] * 4096
-                             : smem + rr_addr[ks] + sr * TILE_BYTES + idx[q] * 4096;
-    if (isA[q]) fa[idx[q]] = *reinterpret_cast<const bf16x8_t*>(src);
-    else fb[idx[q]] = *reinterpret_cast<const bf16x8_t*>(src);
-  };
-  // prologue: staged 0, direct 0, staged 1, direct 1 requested; tile 0 made ready; staged 2 requested
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-#pragma unroll
-    for (int q = 0; q < 8; ++q) mr.issue(q, h);
-    mr.next_tile();
-#pragma unroll
-    for (int q = 0; q < 8; ++q) kd.issue(q, smem + (2 + h) * TILE_BYTES, wave);
-    kd.next_tile();
-  }
-  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-#pragma unroll
-  for (int q = 0; q < 8; ++q) mr.commit(q, lds_addr(smem), 0);
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    rfrag_mc(0, 0, q, xa, xb);
-    mr.issue(q, 0);
-  }
-  mr.next_tile();
-  auto mc_iteration = [&](const int t6) __attribute__((always_inline)) {
-    const int nsr = (t6 & 1) ^ 1;                    // slot and register set of the staged tile t+1
-    char* d2 = smem + (2 + (t6 + 2) % 3) * TILE_BYTES;   // receives the direct tile t+2
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag_mc(t6, 1, q, ya, yb);
-      if (q < 4) kd.issue(q, d2, wave);
-      mma2(q, xa, xb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag_mc(t6, 2, q, xa, xb);
-      if (q < 4) kd.issue(4 + q, d2, wave);
-      mma2(q, ya, yb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    kd.next_tile();
-    // pending, oldest first: staged t+1, direct t+1, staged t+2, direct t+2 (8 loads each)
-    asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag_mc(t6, 3, q, ya, yb);
-      mr.commit(q, lds_addr(smem + nsr * TILE_BYTES), nsr);
-      mma2(q, xa, xb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // tile t+1 complete in LDS for every wavefront, and nobody reads tile t's slots any more
-    asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      rfrag_mc((t6 + 1) % 6, 0, q, xa, xb);
-      mr.issue(q, nsr);
-      mma2(q, ya, yb);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    mr.next_tile();
-  };
-  int kt = 0;
-  for (; kt + 6 <= nk; kt += 6) {
-    mc_iteration(0);
-    mc_iteration(1);
-    mc_iteration(2);
-    mc_iteration(3);
-    mc_iteration(4);
-    mc_iteration(5);
-  }
-  if (kt < nk) mc_iteration(0);
-  if (kt + 1 < nk) mc_iteration(1);
-  if (kt + 2 < nk) mc_iteration(2);
-  if (kt + 3 < nk) mc_iteration(3);
-  if (kt + 4 < nk) mc_iteration(4);
-  } else {
-  // ---- (KC,KC): ring of five 32 KB slots ------------------------------------------------------
+  {
+  // ---- main loop: ring of five 32 KB slots -----------------------------------------------------
   // Operand tiles alternate through the slots: A of K tile t in slot 2t mod 5, B in slot 2t+1 mod 5.
   // While K tile t is multiplied, A(t+1), B(t+1) are landing or landed and A(t+2) is requested
   // during the first two k-steps into the slot B(t-1) left; after the barrier that ends the reads
@@ -438,36 +344,67 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   // barrier, and the wait before the barrier leaves the youngest 8 loads pending.  With two 64 KB
   // stages the loads of a K tile were requested and drained within that tile's own time, and the
   // direct-load stream alone (no MFMA, no fragment reads) took as long as the whole kernel.
-  uint32_t ra_addr[3][4], rb_addr[3][4];   // [slot pair][k-step]; the odd slot of a pair is an immediate away
+  // [slot pair][x]; the odd slot of a pair is an immediate away.  x = k-step for a K-contiguous operand
+  // (whose swizzle depends on it; the fragment index is an immediate), x = fragment for a
+  // rows-contiguous one (the other way round).
+  uint32_t ra_addr[3][4], rb_addr[3][4];
 #pragma unroll
   for (int pr = 0; pr < 3; ++pr)
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const uint32_t sw = (uint32_t)((((ks * 2 + fk) ^ lds_swz(frow)) & 7) << 4);
-      ra_addr[pr][ks] = (uint32_t)(pr * 2 * TILE_BYTES + (wm * 128 + frow) * 128) + sw;
-      rb_addr[pr][ks] = (uint32_t)(pr * 2 * TILE_BYTES + (wn * 128 + frow) * 128) + sw;
+    for (int x = 0; x < 4; ++x) {
+      const uint32_t sw = (uint32_t)((((x * 2 + fk) ^ lds_swz(frow)) & 7) << 4);
+      ra_addr[pr][x] = (uint32_t)(pr * 2 * TILE_BYTES) +
+                       (LA == OP_KC ? (uint32_t)((wm * 128 + frow) * 128) + sw : LoaderMC::frag_off(wm, x, lane));
+      rb_addr[pr][x] = (uint32_t)(pr * 2 * TILE_BYTES) +
+                       (LB == OP_KC ? (uint32_t)((wn * 128 + frow) * 128) + sw : LoaderMC::frag_off(wn, x, lane));
     }
   auto rfrag_ring = [&](int sa, int sb, int ks, int q, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
     constexpr int isA[8] = {1, 0, 0, 1, 0, 0, 1, 1};
     constexpr int idx[8] = {0, 0, 1, 1, 2, 3, 2, 3};
-    if (isA[q])
-      fa[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + ra_addr[sa >> 1][ks] + (sa & 1) * TILE_BYTES + idx[q] * 4096);
-    else
-      fb[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + rb_addr[sb >> 1][ks] + (sb & 1) * TILE_BYTES + idx[q] * 4096);
+    if (isA[q]) {
+      if (LA == OP_KC)
+        fa[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + ra_addr[sa >> 1][ks] + (sa & 1) * TILE_BYTES + idx[q] * 4096);
+      else
+        fa[idx[q]] = lds_read_frag_tr(smem + ra_addr[sa >> 1][idx[q]] + (sa & 1) * TILE_BYTES + ks * 8192);
+    } else {
+      if (LB == OP_KC)
+        fb[idx[q]] = *reinterpret_cast<const bf16x8_t*>(smem + rb_addr[sb >> 1][ks] + (sb & 1) * TILE_BYTES + idx[q] * 4096);
+      else
+        fb[idx[q]] = lds_read_frag_tr(smem + rb_addr[sb >> 1][idx[q]] + (sb & 1) * TILE_BYTES + ks * 8192);
+    }
   };
   int a_to_switch = p.A2 ? nk1 : -1, b_to_switch = a_to_switch;
   auto next_A = [&]() {
-    if (--a_to_switch == 0) ka.win.set(p.A2, ((int64_t)p.M * p.lda - (p.kc_skip - rot)) * 2); else ka.next_tile();
+    if constexpr (LA == OP_KC) {
+      if (--a_to_switch == 0) ka.win.set(p.A2, ((int64_t)p.M * p.lda - (p.kc_skip - rot)) * 2); else ka.next_tile();
+    } else {
+      da.next_tile();
+    }
   };
   auto next_B = [&]() {
-    if (--b_to_switch == 0) kb_.win.set(p.B2, ((int64_t)p.N * p.ldb - (p.kc_skip - rot)) * 2); else kb_.next_tile();
+    if constexpr (LB == OP_KC) {
+      if (--b_to_switch == 0) kb_.win.set(p.B2, ((int64_t)p.N * p.ldb - (p.kc_skip - rot)) * 2); else kb_.next_tile();
+    } else {
+      if (--b_to_switch == 0) db.win.set(p.B2, (int64_t)p.K2 * p.ldb * 2); else db.next_tile();
+    }
+  };
+  constexpr bool OPAQUE = (LA == OP_MC || LB == OP_MC);   // see lds_dma_16
+  auto issue_A = [&](int q, char* tile) {
+    if constexpr (LA != OP_KC) da.issue(q, tile, wave);
+    else if constexpr (OPAQUE) ka.issue_opaque(q, tile, wave);
+    else ka.issue(q, tile, wave);
+  };
+  auto issue_B = [&](int q, char* tile) {
+    if constexpr (LB != OP_KC) db.issue(q, tile, wave);
+    else if constexpr (OPAQUE) kb_.issue_opaque(q, tile, wave);
+    else kb_.issue(q, tile, wave);
   };
   // prologue: A0, B0, A1, B1 into slots 0..3
 #pragma unroll
   for (int h = 0; h < 4; ++h) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      if (h & 1) kb_.issue(q, smem + h * TILE_BYTES, wave); else ka.issue(q, smem + h * TILE_BYTES, wave);
+      if (h & 1) issue_B(q, smem + h * TILE_BYTES); else issue_A(q, smem + h * TILE_BYTES);
     }
     if (h & 1) next_B(); else next_A();
   }
@@ -483,14 +420,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       rfrag_ring(sa, sb, 1, q, ya, yb);
-      if (q < 4) ka.issue(q, smem + ia * TILE_BYTES, wave);
+      if (q < 4) issue_A(q, smem + ia * TILE_BYTES);
       mma2(q, xa, xb);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       rfrag_ring(sa, sb, 2, q, xa, xb);
-      if (q < 4) ka.issue(4 + q, smem + ia * TILE_BYTES, wave);
+      if (q < 4) issue_A(4 + q, smem + ia * TILE_BYTES);
       mma2(q, ya, yb);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -509,7 +446,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       rfrag_ring(na, nb, 0, q, xa, xb);
-      kb_.issue(q, smem + sa * TILE_BYTES, wave);
+      issue_B(q, smem + sa * TILE_BYTES);
       mma2(q, ya, yb);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -715,10 +652,10 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
   // buffer offsets are 32-bit: every operand must stay below 2 GiB
   const int64_t lim = 0x7fffffff;
-  const int64_t kmc = a.K_mc > 0 ? a.K_mc : a.K;
-  const int64_t abytes = (la == OP_KC ? (int64_t)a.M : kmc) * a.lda * 2;
-  const int64_t bbytes = (lb == OP_KC ? (int64_t)a.N : kmc) * a.ldb * 2;
+  const int64_t abytes = (la == OP_KC ? (int64_t)a.M : (int64_t)a.K) * a.lda * 2;
+  const int64_t bbytes = (lb == OP_KC ? (int64_t)a.N : (int64_t)std::max(a.K, a.K2)) * a.ldb * 2;
   if (abytes > lim || bbytes > lim) return hipErrorInvalidValue;
+  if (a.A2 && la != OP_KC) return hipErrorInvalidValue;   // a second operand pair needs a K-contiguous A
   // so are the outputs' (buffer stores)
   if ((int64_t)a.M * a.N * (epi == EPI_F32 ? 4 : 2) > lim) return hipErrorInvalidValue;
   if (la == OP_KC && lb == OP_KC) {
@@ -730,10 +667,13 @@ hipError_t stem_gemm_bf16(stem_ctx* ctx, int kid, int la, int lb, int epi, const
     if (epi == EPI_GATE_UPE) return launch<OP_KC, OP_KC, EPI_GATE_UPE>(ctx, kid, a, s);
     if (epi == EPI_DH_UP) return launch<OP_KC, OP_KC, EPI_DH_UP>(ctx, kid, a, s);
     if (epi == EPI_DH_UPE) return launch<OP_KC, OP_KC, EPI_DH_UPE>(ctx, kid, a, s);
-  } else if (la == OP_KC && lb == OP_MC) {   // weight gradients: one operand rows-contiguous
-    if (epi == EPI_F32) return launch<OP_KC, OP_MC, EPI_F32>(ctx, kid, a, s);
-  } else if (la == OP_MC && lb == OP_KC) {
-    if (epi == EPI_F32) return launch<OP_MC, OP_KC, EPI_F32>(ctx, kid, a, s);
+  } else if (la == OP_KC && lb == OP_MC) {  // activation gradients: the weight as stored, rows-contiguous
+    if (epi == EPI_BF16) return launch<OP_KC, OP_MC, EPI_BF16>(ctx, kid, a, s);
+    if (epi == EPI_DH) return launch<OP_KC, OP_MC, EPI_DH>(ctx, kid, a, s);
+    if (epi == EPI_DH_UP) return launch<OP_KC, OP_MC, EPI_DH_UP>(ctx, kid, a, s);
+    if (epi == EPI_DH_UPE) return launch<OP_KC, OP_MC, EPI_DH_UPE>(ctx, kid, a, s);
+  } else if (la == OP_MC && lb == OP_MC) {  // weight gradients: both operands [K, rows], rows contiguous
+    if (epi == EPI_F32) return launch<OP_MC, OP_MC, EPI_F32>(ctx, kid, a, s);
   }
   return hipErrorInvalidValue;
 }

@@ -143,32 +143,6 @@ __global__ void dh_epilogue_f32_kernel(const float* __restrict__ dH, const float
   *reinterpret_cast<float4*>(dG + t * F + c) = make_float4(dg[0], dg[1], dg[2], dg[3]);
 }
 
-// out[c, r] = in[r, c] for bf16; out has leading dimension ldo >= R and columns R..ldo-1 of
-// every row are written as zeros.  64x64 tiles through LDS, 16-byte global accesses.
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ in, int R, int C,
-                                                             bf16_t* __restrict__ out, int ldo) {
-  __shared__ bf16_t tile[64][72];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int r = (t >> 3) + 32 * h, cc = (t & 7) * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r0 + r < R && c0 + cc < C) v = *reinterpret_cast<const uint4*>(in + (size_t)(r0 + r) * C + c0 + cc);
-    *reinterpret_cast<uint4*>(&tile[r][cc]) = v;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int c = (t >> 3) + 32 * h, rr = (t & 7) * 8;
-    if (c0 + c >= C || r0 + rr >= ldo) continue;
-    bf16_t w[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) w[q] = tile[rr + q][c];
-    *reinterpret_cast<uint4*>(out + (size_t)(c0 + c) * ldo + r0 + rr) = *reinterpret_cast<const uint4*>(w);
-  }
-}
-
 }  // namespace
 
 // Zero fill by a kernel rather than hipMemsetAsync, so that every call of the library can be recorded
@@ -181,14 +155,6 @@ hipError_t stem_fill_zero(void* p, size_t bytes, hipStream_t s) {   // bytes is 
   const size_t words = bytes / 4;
   const unsigned grid = (unsigned)std::min<size_t>((words + 255) / 256, 2048);
   hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, static_cast<uint32_t*>(p), words);
-  return hipGetLastError();
-}
-
-hipError_t stem_transpose_bf16(stem_ctx* ctx, const void* in, int R, int C, void* out, int ldo, hipStream_t s) {
-  if (R <= 0 || C <= 0) return hipSuccess;
-  ProfScope ps(ctx, K_TRANSPOSE, s);
-  dim3 grid((C + 63) / 64, (ldo + 63) / 64);
-  hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, (const bf16_t*)in, R, C, (bf16_t*)out, ldo);
   return hipGetLastError();
 }
 

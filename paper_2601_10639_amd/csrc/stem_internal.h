@@ -27,7 +27,6 @@ enum StemKernelId {
   K_SEG_COMBINE,
   K_ADAMW,
   K_ROW_COPY,        // host-resident rows -> compact device table
-  K_TRANSPOSE,       // bf16 operand transposes ahead of the backward GEMMs
   K_SPLITK_REDUCE,   // sum of split-K partial products
   K_GEMM_UP,         // Up = X Wu^T (dense SwiGLU and the additive variant)
   K_GEMM_DWUP,       // dWu = dV^T X
@@ -49,10 +48,7 @@ struct stem_ctx {
   void* H_ws;            // [max_tokens, F] context dtype
   void* dG_ws;           // [max_tokens, F] context dtype
   void* dH_ws;           // [max_tokens, F] fp32, STEM_F32 only
-  void* WT_ws;           // [F*d] bf16: a weight matrix transposed (backward)
-  void* actT_ws;         // [d, round_up(max_tokens, 64)] bf16: dy or x transposed (backward)
   void* Up_ws;           // [max_tokens, F] bf16, allocated by the first stem_ffn_up_* call
-  void* WT2_ws;          // [F*d] bf16, second transposed weight, ditto
   float* splitk_ws;      // STEM_SPLITK_WS_BYTES: fp32 partial products of the few-row GEMMs
   float* dw_ws;          // [dw_ksplit][d*F] fp32 partial weight gradients, when the layer is narrow
   int dw_ksplit;         // K slices of the weight-gradient GEMMs (1 = no split)
@@ -141,7 +137,6 @@ struct GemmArgs {
   const bf16_t* A; // M-side operand
   const bf16_t* B; // N-side operand
   int M, N, K;
-  int K_mc;        // k-rows that exist in a rows-contiguous operand (0 = K); the rest read as zero
   int lda, ldb;    // leading dimensions of the stored operands
   void* C;         // EPI_BF16 / EPI_F32 output, ld = N
   const bf16_t* residual;  // EPI_BF16_RES (and the few-row kernel when not null): [M,N] bf16 added in fp32 before rounding
@@ -182,7 +177,6 @@ hipError_t stem_gemm_skinny_bf16(stem_ctx* ctx, int kid, int epi, const GemmArgs
 hipError_t stem_sgemm(stem_ctx* ctx, int kid, const float* A, int64_t sam, int64_t sak, const float* B,
                       int64_t sbn, int64_t sbk, float* C, int M, int N, int K, int accumulate, hipStream_t s);
 // out[c,r] = in[r,c] (bf16), leading dimension ldo, zero padding beyond R
-hipError_t stem_transpose_bf16(stem_ctx* ctx, const void* in, int R, int C, void* out, int ldo, hipStream_t s);
 hipError_t stem_fill_zero(void* p, size_t bytes, hipStream_t s);   // a kernel, not a memset node
 // H = SiLU(G) * E[ids]; is_bf16 selects the element type of G, E, H
 hipError_t stem_silu_gather(stem_ctx* ctx, int is_bf16, const void* G, const int32_t* ids, const void* E,

@@ -412,7 +412,7 @@ def stem_profile_read(ctx: StemCtx) -> dict:
     return out
 
 
-STEM_PEAK_MFMA_BF16, STEM_PEAK_HBM_READ, STEM_PEAK_HBM_COPY = 0, 1, 2
+STEM_PEAK_MFMA_BF16, STEM_PEAK_HBM_READ, STEM_PEAK_HBM_COPY, STEM_PEAK_MFMA_BF16_DATA = 0, 1, 2, 3
 
 
 def stem_measure_peak(what: int, buf_a, buf_b=None, repeats: int = 3, stream=None) -> float:
