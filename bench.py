@@ -104,14 +104,20 @@ def measure_peaks(dev):
     from paper_2601_10639_amd import stemlib as L
     a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
     b = torch.empty_like(a)
+    g = torch.Generator(device=dev).manual_seed(7)
+    normal = torch.randn(1 << 16, device=dev, generator=g).to(torch.bfloat16)   # operands like the layer's own
+    sink = torch.zeros(64, device=dev)
     peaks = {
         "mfma_bf16_tflops": round(L.stem_measure_peak(L.STEM_PEAK_MFMA_BF16, a, None, repeats=3), 1),
+        "mfma_bf16_unit_normal_data_tflops": round(L.stem_measure_peak(L.STEM_PEAK_MFMA_BF16_DATA, normal, sink, repeats=3), 1),
         "hbm_read_gbs": round(L.stem_measure_peak(L.STEM_PEAK_HBM_READ, a, b, repeats=5), 1),
         "hbm_copy_gbs": round(L.stem_measure_peak(L.STEM_PEAK_HBM_COPY, a, b, repeats=5), 1),
-        "how": "stem_measure_peak: loop of independent 32x32x16 bf16 MFMAs on registers (7 ms); 1 GiB streaming read; "
-               "1 GiB streaming copy, bytes read + written; best of 3 / 5 / 5 runs between HIP events",
+        "how": "stem_measure_peak: loop of independent 32x32x16 bf16 MFMAs on registers with near-constant operands (7 ms), "
+               "the same MFMA count on unit-normal operands (the chip is power-limited: the more operand bits toggle, "
+               "the lower the clock it sustains); 1 GiB streaming read; 1 GiB streaming copy, bytes read + written; "
+               "best of 3 / 3 / 5 / 5 runs between HIP events",
     }
-    del a, b
+    del a, b, normal, sink
     torch.cuda.empty_cache()
     return peaks
 
@@ -251,6 +257,10 @@ def bench_layer(args, shape, dev, steps, warmup, peaks, detail):
     prof = L.stem_profile_read(ctx)
     # the stand-alone SiLU * gather kernel at this shape (what backward runs when H was not saved)
     if variant == "stem":
+        for _ in range(2):   # the context's own H buffer is touched for the first time here
+            L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, None, dx, dWg,
+                                dWd, dU)
+        L.stem_profile_read(ctx)
         L.stem_profile_reset(ctx)
         for _ in range(10):
             L.stem_ffn_backward(ctx, inp["dy"], inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], E, G, None, dx, dWg,
@@ -276,6 +286,7 @@ def bench_layer(args, shape, dev, steps, warmup, peaks, detail):
             k["frac_mfma_peak"] = round(k["tflops"] / peak_tf, 4)
             if bf16:
                 k["frac_of_measured"] = round(k["tflops"] / peaks["mfma_bf16_tflops"], 4)
+                k["frac_of_measured_on_data"] = round(k["tflops"] / peaks["mfma_bf16_unit_normal_data_tflops"], 4)
         elif name in algo_bytes:
             k["algorithmic_bytes"] = algo_bytes[name]
             k["gbs"] = round(algo_bytes[name] / (avg * 1e-3) / 1e9, 1)
@@ -316,12 +327,14 @@ def bench_layer(args, shape, dev, steps, warmup, peaks, detail):
         "unit": "TFLOP/s",
         "frac": round(gemms[dom]["tflops"] / peak_tf, 4),
         "frac_of_measured": round(gemms[dom]["tflops"] / peaks["mfma_bf16_tflops"], 4) if bf16 else None,
+        "frac_of_measured_on_data": round(gemms[dom]["tflops"] / peaks["mfma_bf16_unit_normal_data_tflops"], 4) if bf16 else None,
         "traffic": traffic.get(dom),
         "counters": counters.get(dom),
         "traffic_and_counters_source": "profiles/%s, profiles/%s (committed rocprofv3 summaries of this command)" % (tname, cname),
         "all_gemms_tflops": round(all_tf, 2),
         "all_gemms_frac": round(all_tf / peak_tf, 4),
         "all_gemms_frac_of_measured": round(all_tf / peaks["mfma_bf16_tflops"], 4) if bf16 else None,
+        "all_gemms_frac_of_measured_on_data": round(all_tf / peaks["mfma_bf16_unit_normal_data_tflops"], 4) if bf16 else None,
     }
 
     out = {
