@@ -59,12 +59,9 @@ constexpr uint32_t OOB = 0x80000000u;  // a buffer offset beyond any operand: re
 __device__ __forceinline__ uint32_t lds_addr(const char* p) {   // p points into LDS
   return (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<char*>(p);
 }
-// chunk slot swizzle of a tile row (only bits 1..4 of the row: the same for rows 32 apart, so the
-// fragments of a wavefront's four 32-row blocks sit at one address plus immediates)
+// chunk slot swizzle of a row of a K-contiguous tile (only bits 1..4 of the row: the same for rows 32
+// apart, so the fragments of a wavefront's four 32-row blocks sit at one address plus immediates)
 __device__ __forceinline__ int lds_swz(int row) { return ((row >> 1) ^ (((row >> 3) & 3) << 1)) & 7; }
-__device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
-  return (uint32_t)(row * 128 + (((chunk ^ lds_swz(row)) & 7) << 4));
-}
 
 // A buffer resource that moves along the operand: base advances, the record count shrinks.
 // The descriptor is rebuilt once per K tile (a handful of scalar instructions), not per load.
@@ -334,7 +331,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   };
   const int touch_at = nk > 8 ? ((nk - 6) & ~1) : -1;   // an even K tile index a few tiles before the end
   bf16x8_t xa[4], xb[4], ya[4], yb[4];
-  {
   // ---- main loop: ring of five 32 KB slots -----------------------------------------------------
   // Operand tiles alternate through the slots: A of K tile t in slot 2t mod 5, B in slot 2t+1 mod 5.
   // While K tile t is multiplied, A(t+1), B(t+1) are landing or landed and A(t+2) is requested
@@ -408,8 +404,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     }
     if (h & 1) next_B(); else next_A();
   }
+  // A0 and B0 have landed; A1 and B1 stay in flight across the barrier.  (A plain __syncthreads() here
+  // makes the compiler wait for every direct-to-LDS load it knows of, i.e. for all four tiles: stamps
+  // inside the kernel, 8-9 K clocks to the first MFMA against 5-6 K.)
   asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  __syncthreads();
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int q = 0; q < 8; ++q) rfrag_ring(0, 1, 0, q, xa, xb);
   // K tile t with t mod 5 == tmod (all slot numbers are compile-time constants)
@@ -466,7 +466,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   if (kt + 1 < nk) ring_iteration(1);
   if (kt + 2 < nk) ring_iteration(2);
   if (kt + 3 < nk) ring_iteration(3);
-  }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (TOUCH)   // end of the touched registers' reservation
     asm volatile("" ::"v"(touched[0]), "v"(touched[1]), "v"(touched[2]), "v"(touched[3]));
