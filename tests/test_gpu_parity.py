@@ -546,3 +546,22 @@ def test_sparse_adamw_three_steps_on_shared_gradients(dtype):
         np.testing.assert_array_equal(got[touched], want[touched])
         np.testing.assert_array_equal(got[~touched], E0.float().cpu().numpy()[~touched])
     ctx.close()
+
+
+def test_on_box_peak_measurements_run_and_order_as_expected():
+    """stem_measure_peak: every kind returns a positive rate; the MFMA loop on all-zero operands is not
+    slower than on unit-normal ones (the chip sustains a lower clock the more operand bits toggle)."""
+    a = torch.zeros(1 << 24, dtype=torch.uint8, device=DEV)
+    b = torch.empty_like(a)
+    assert L.stem_measure_peak(L.STEM_PEAK_MFMA_BF16, a, None, repeats=1) > 100.0
+    assert L.stem_measure_peak(L.STEM_PEAK_HBM_READ, a, b, repeats=2) > 100.0
+    assert L.stem_measure_peak(L.STEM_PEAK_HBM_COPY, a, b, repeats=2) > 100.0
+    sink = torch.zeros(64, device=DEV)
+    zeros = torch.zeros(1 << 16, dtype=torch.bfloat16, device=DEV)
+    normal = inputs.normal((1 << 16,), 1.0, 5, torch.bfloat16, DEV)
+    on_zeros = L.stem_measure_peak(L.STEM_PEAK_MFMA_BF16_DATA, zeros, sink, repeats=2)
+    on_normal = L.stem_measure_peak(L.STEM_PEAK_MFMA_BF16_DATA, normal, sink, repeats=2)
+    assert on_normal > 100.0 and on_zeros >= 0.98 * on_normal, (on_zeros, on_normal)
+    with pytest.raises(L.StemError):   # the data loop needs its second buffer
+        L.stem_measure_peak(L.STEM_PEAK_MFMA_BF16_DATA, zeros, None, repeats=1)
+

@@ -94,6 +94,49 @@ def test_c3_1b_shaped_layer_full_size():
     _full_size_case("C3", seed=22)
 
 
+@pytest.mark.parametrize("with_table", [False, True])
+def test_c2_shaped_dense_and_additive_layers_full_size(with_table):
+    """The dense SwiGLU layer and the additive variant at the 350M shape, every element of every output
+    against one run of the oracle over the whole batch.  At this size the backward products read the
+    weights and both operands of the weight gradients rows-contiguous over many K tiles, dx runs over
+    the concatenated K range of two operand pairs, and the weight gradients are cut along K."""
+    shape = inputs.SHAPES["C2"]
+    T, d, F, V = shape.tokens, shape.d_model, shape.d_ff, shape.vocab
+    tol = Hn.TOL["bf16"]
+    inp = inputs.layer_inputs(shape, seed=23, device=DEV)
+    Wu = inputs.normal((F, d), 0.02, 24, torch.bfloat16, DEV)
+    E = inp["E"] if with_table else None
+    ids = inp["ids"] if with_table else None
+    ctx = Hn.make_ctx(shape, T, reserve=L.STEM_RESERVE_UP)
+    bf = torch.bfloat16
+    y = torch.empty(T, d, dtype=bf, device=DEV)
+    G, Up, H, dV = (torch.empty(T, F, dtype=bf, device=DEV) for _ in range(4))
+    dx = torch.empty(T, d, dtype=bf, device=DEV)
+    dWg, dWu = (torch.empty(F, d, dtype=torch.float32, device=DEV) for _ in range(2))
+    dWd = torch.empty(d, F, dtype=torch.float32, device=DEV)
+    L.stem_ffn_up_forward(ctx, inp["x"], ids, inp["W_gate"], Wu, inp["W_down"], E, y, G, Up, H)
+    L.stem_ffn_up_backward(ctx, inp["dy"], inp["x"], ids, inp["W_gate"], Wu, inp["W_down"], E, G, Up, H, dx, dWg, dWu,
+                           dWd, dV)
+    L.stem_sync_status(ctx)
+    ids_np = inp["ids"].cpu().numpy()
+    uniq_all, remap_all = np.unique(ids_np, return_inverse=True)
+    E_u = _rows(inp["E"], uniq_all) if with_table else None   # the table cut down to the rows the batch names
+    Wg, Wd, Wu64 = inputs.to_f64(inp["W_gate"]), inputs.to_f64(inp["W_down"]), inputs.to_f64(Wu)
+    x_all, dy_all = inputs.to_f64(inp["x"]), inputs.to_f64(inp["dy"])
+    ref, fw = O.up_forward(x_all, remap_all, Wg, Wu64, Wd, E_u)
+    errs = {"y": Hn.max_rel(inputs.to_f64(y), ref), "G": Hn.max_rel(inputs.to_f64(G), fw["g"]),
+            "Up": Hn.max_rel(inputs.to_f64(Up), fw["up"]), "H": Hn.max_rel(inputs.to_f64(H), fw["h"])}
+    del ref, fw
+    bw = O.up_backward(dy_all, x_all, remap_all, Wg, Wu64, Wd, E_u)
+    errs.update({"dx": Hn.max_rel(inputs.to_f64(dx), bw["dx"]), "dV": Hn.max_rel(inputs.to_f64(dV), bw["dV"]),
+                 "dW_gate": Hn.max_rel(inputs.to_f64(dWg), bw["dW_gate"]), "dW_up": Hn.max_rel(inputs.to_f64(dWu), bw["dW_up"]),
+                 "dW_down": Hn.max_rel(inputs.to_f64(dWd), bw["dW_down"])})
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
+    print("C2 dense" if not with_table else "C2 additive", {k: float("%.3g" % v) for k, v in errs.items()})
+    ctx.close()
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_c4_decode_chain_sixteen_layers(fused):
     """256 single tokens through 16 stacked 1B-shaped layers, residual stream rounded to bf16 between
