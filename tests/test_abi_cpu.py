@@ -95,3 +95,19 @@ def test_binding_refuses_wrong_dtypes_before_calling():
     x = torch.zeros(4, 64, dtype=torch.float32)
     with pytest.raises(TypeError):
         L.stem_ffn_forward(Fake(), x, torch.zeros(4, dtype=torch.int32), x, x, x, x)
+
+
+def test_early_touch_of_gathered_rows_stays_inside_the_table():
+    """The gate product touches, a few K tiles before its epilogue, the two 128-byte lines of the table
+    row that a wavefront's 128 output columns will read.  Host-side model of those addresses (column
+    of the wavefront's quadrant, second line only if the row is that wide) over every d_ff the bf16
+    path accepts up to 1024 and the first and last table rows: each 4-byte touch lies inside the row."""
+    for F in range(64, 1025, 64):
+        ntn = (F + 255) // 256
+        for tn in range(ntn):
+            for wn in (0, 1):
+                ncol = tn * 256 + wn * 128
+                col = ncol if ncol < F else 0
+                second = col + 64 if col + 64 < F else col
+                for first_elem in (col, second):
+                    assert 0 <= first_elem and first_elem * 2 + 4 <= F * 2, (F, tn, wn, first_elem)
