@@ -292,6 +292,8 @@ def bench_layer(args, shape, dev, steps, warmup, peaks, detail):
             k["gbs"] = round(algo_bytes[name] / (avg * 1e-3) / 1e9, 1)
             k["frac_hbm_peak"] = round(k["gbs"] / PEAK_HBM_GBS, 4)
             k["frac_of_measured_copy"] = round(k["gbs"] / peaks["hbm_copy_gbs"], 4)
+        if name == "sort_fused" and overlap_sort:
+            k["note"] = "one workgroup on a second stream under the backward GEMMs: wall time while it waits for a compute unit; 39 us when it runs alone"
         kernels[name] = k
     # the segmented sum (G3) is everything it launches: the chunk sums and the sums over border-crossing runs
     if "seg_reduce" in kernels:
