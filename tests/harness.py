@@ -33,8 +33,8 @@ def make_ctx(shape: inputs.StemShape, max_tokens: int, reserve: int = 0) -> L.St
     return L.stem_create(shape.d_model, shape.d_ff, shape.vocab, dt, max_tokens, 0, reserve=reserve)
 
 
-def hip_forward_backward(ctx, inp, save_H=True, want_dx=True):
-    """forward + backward through libstem; returns device tensors."""
+def hip_forward_backward(ctx, inp, save_H=True, want_dx=True, after_forward=None):
+    """forward + backward through libstem; returns device tensors.  `after_forward()` runs between the two calls."""
     dev = inp["x"].device
     dt = inp["x"].dtype
     T, d = inp["x"].shape
@@ -43,6 +43,8 @@ def hip_forward_backward(ctx, inp, save_H=True, want_dx=True):
     G = torch.empty(T, F, dtype=dt, device=dev)
     H = torch.empty(T, F, dtype=dt, device=dev) if save_H else None
     L.stem_ffn_forward(ctx, inp["x"], inp["ids"], inp["W_gate"], inp["W_down"], inp["E"], y, G, H)
+    if after_forward is not None:
+        after_forward()
     dx = torch.empty(T, d, dtype=dt, device=dev) if want_dx else None
     dWg = torch.empty(F, d, dtype=torch.float32, device=dev)
     dWd = torch.empty(d, F, dtype=torch.float32, device=dev)
