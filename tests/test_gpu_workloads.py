@@ -1,6 +1,7 @@
 """GPU parity at the full workload sizes (every element of C2 and C3 against a whole-batch oracle run;
-sampled tokens for the 65536-token host-resident case), the stacked decode chain, and the
-host-resident-table mode.  All through the C ABI."""
+sampled tokens for the 65536-token host-resident case; sampled tokens and sampled columns at the largest
+token count a context accepts), the stacked decode chain, and the host-resident-table mode.  All through
+the C ABI."""
 import os
 
 import numpy as np
@@ -92,6 +93,65 @@ def test_c2_350m_shaped_layer_full_size():
 
 def test_c3_1b_shaped_layer_full_size():
     _full_size_case("C3", seed=22)
+
+
+def test_largest_token_count_a_bf16_context_accepts():
+    """T = 131071 tokens at d_ff = 8192: the [T, d_ff] activations end 16 KiB below 2^31 bytes, the largest
+    the 32-bit buffer offsets of the products allow (stem_create refuses one token more).  T is odd, so every
+    product has a ragged last tile and the weight-gradient products a ragged last K tile.  The oracle
+    runs (a) the whole layer on a sample of tokens that includes the first and last rows and both sides
+    of tile borders (y, G, H, dx, dU rows) and (b) the layer cut down to a sample of d_ff columns, first
+    and last included, on ALL tokens, which yields those columns of G, H, dU and dW_down, those rows of
+    dW_gate and those columns of the table-gradient rows exactly.  Sort outputs are compared bit for bit."""
+    d, F, V = 1024, 8192, 4096
+    T = (2 ** 31 - 1) // (2 * F)
+    assert T == 131071
+    shape = inputs.StemShape("bf16-max-tokens", d, F, V, 1, T, "bf16")
+    with pytest.raises(L.StemError):
+        Hn.make_ctx(shape, T + 1)
+    tol = Hn.TOL["bf16"]
+    inp = inputs.layer_inputs(shape, seed=31, device=DEV, tokens=T)
+    ctx = Hn.make_ctx(shape, T)
+    out = Hn.hip_forward_backward(ctx, inp)
+    eg = Hn.hip_embed_grad(ctx, inp["ids"], out["dU"], V)
+    L.stem_sync_status(ctx)
+    ids = inp["ids"].cpu().numpy()
+    U = Hn.check_integers(eg, ids)
+    uniq_all, remap_all = np.unique(ids, return_inverse=True)
+    Wg, Wd = inputs.to_f64(inp["W_gate"]), inputs.to_f64(inp["W_down"])
+    E_u = _rows(inp["E"], uniq_all)
+    rng = np.random.default_rng(31)
+
+    # (a) whole layer, sampled tokens
+    ts = np.unique(np.concatenate([[0, 1, 255, 256, 257, 65535, 65536, T - 258, T - 257, T - 256, T - 255, T - 2, T - 1],
+                                   rng.integers(0, T, 51)]))
+    x_s, dy_s = _rows(inp["x"], ts), _rows(inp["dy"], ts)
+    y, fw = O.ffn_forward(x_s, remap_all[ts], Wg, Wd, E_u)
+    bw = O.ffn_backward(dy_s, x_s, remap_all[ts], Wg, Wd, E_u)
+    errs = {"y": Hn.max_rel(_rows(out["y"], ts), y), "G": Hn.max_rel(_rows(out["G"], ts), fw["g"]),
+            "H": Hn.max_rel(_rows(out["H"], ts), fw["h"]), "dx": Hn.max_rel(_rows(out["dx"], ts), bw["dx"]),
+            "dU": Hn.max_rel(_rows(out["dU"], ts), bw["dU"])}
+    del y, fw, bw
+
+    # (b) sampled d_ff columns, all tokens
+    fs = np.unique(np.concatenate([[0, 1, 7, 8, 255, 256, F - 9, F - 8, F - 1], rng.integers(0, F, 15)]))
+    fs_t = torch.as_tensor(fs, device=DEV)
+    x_all, dy_all = inputs.to_f64(inp["x"]), inputs.to_f64(inp["dy"])
+    _, fw = O.ffn_forward(x_all, remap_all, Wg[fs], Wd[:, fs], E_u[:, fs])
+    errs["G cols"] = Hn.max_rel(inputs.to_f64(out["G"][:, fs_t]), fw["g"])
+    errs["H cols"] = Hn.max_rel(inputs.to_f64(out["H"][:, fs_t]), fw["h"])
+    del fw
+    bw = O.ffn_backward(dy_all, x_all, remap_all, Wg[fs], Wd[:, fs], E_u[:, fs])
+    errs["dU cols"] = Hn.max_rel(inputs.to_f64(out["dU"][:, fs_t]), bw["dU"])
+    errs["dW_down cols"] = Hn.max_rel(inputs.to_f64(out["dW_down"][:, fs_t]), bw["dW_down"])
+    errs["dW_gate rows"] = Hn.max_rel(inputs.to_f64(out["dW_gate"][fs_t]), bw["dW_gate"])
+    oeg = O.embed_grad(ids, bw["dU"])
+    np.testing.assert_array_equal(oeg["uniq_ids"], uniq_all)
+    errs["dE_rows cols"] = Hn.max_rel(inputs.to_f64(eg["dE_rows"][:U][:, fs_t]), oeg["dE_rows"])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
+    print("T = 131071:", {k: float("%.3g" % v) for k, v in errs.items()}, "n_uniq", U)
+    ctx.close()
 
 
 @pytest.mark.parametrize("with_table", [False, True])
