@@ -154,6 +154,53 @@ def test_largest_token_count_a_bf16_context_accepts():
     ctx.close()
 
 
+def test_widest_layer_a_bf16_context_accepts():
+    """d_model = 8192, d_ff = 65472: the fp32 weight gradients end 2 MiB below 2^31 bytes (stem_create
+    refuses d_ff = 65536).  600 tokens, so the 256x256-tile kernels run every product, with ragged row
+    tiles, 1023 K tiles in dx and 8192 output tiles in each weight gradient.  Checked as in the test
+    above: the whole layer on sampled tokens, and the layer cut down to sampled d_ff columns (first and
+    last included) on all tokens."""
+    d, F, V, T = 8192, 65472, 64, 600
+    with pytest.raises(L.StemError):
+        Hn.make_ctx(inputs.StemShape("bf16-too-wide", d, F + 64, V, 1, T, "bf16"), T)
+    shape = inputs.StemShape("bf16-widest", d, F, V, 1, T, "bf16")
+    tol = Hn.TOL["bf16"]
+    inp = inputs.layer_inputs(shape, seed=32, device=DEV, tokens=T)
+    ctx = Hn.make_ctx(shape, T)
+    out = Hn.hip_forward_backward(ctx, inp)
+    L.stem_sync_status(ctx)
+    ids = inp["ids"].cpu().numpy()
+    E = inputs.to_f64(inp["E"])
+    rng = np.random.default_rng(32)
+    x_all, dy_all = inputs.to_f64(inp["x"]), inputs.to_f64(inp["dy"])
+
+    # (b) sampled d_ff columns, all tokens (before the full weights are widened: less host memory at once)
+    fs = np.unique(np.concatenate([[0, 1, 255, 256, F - 65, F - 64, F - 2, F - 1], rng.integers(0, F, 16)]))
+    fs_t = torch.as_tensor(fs, device=DEV)
+    Wg_s, Wd_s = inputs.to_f64(inp["W_gate"][fs_t]), inputs.to_f64(inp["W_down"][:, fs_t])
+    _, fw = O.ffn_forward(x_all, ids, Wg_s, Wd_s, E[:, fs])
+    errs = {"G cols": Hn.max_rel(inputs.to_f64(out["G"][:, fs_t]), fw["g"]),
+            "H cols": Hn.max_rel(inputs.to_f64(out["H"][:, fs_t]), fw["h"])}
+    bw = O.ffn_backward(dy_all, x_all, ids, Wg_s, Wd_s, E[:, fs])
+    errs["dU cols"] = Hn.max_rel(inputs.to_f64(out["dU"][:, fs_t]), bw["dU"])
+    errs["dW_down cols"] = Hn.max_rel(inputs.to_f64(out["dW_down"][:, fs_t]), bw["dW_down"])
+    errs["dW_gate rows"] = Hn.max_rel(inputs.to_f64(out["dW_gate"][fs_t]), bw["dW_gate"])
+    del fw, bw
+
+    # (a) whole layer, sampled tokens
+    ts = np.unique(np.concatenate([[0, 1, 255, 256, 511, 512, T - 2, T - 1], rng.integers(0, T, 16)]))
+    Wg, Wd = inputs.to_f64(inp["W_gate"]), inputs.to_f64(inp["W_down"])
+    y, fw = O.ffn_forward(x_all[ts], ids[ts], Wg, Wd, E)
+    bw = O.ffn_backward(dy_all[ts], x_all[ts], ids[ts], Wg, Wd, E)
+    errs.update({"y": Hn.max_rel(_rows(out["y"], ts), y), "G": Hn.max_rel(_rows(out["G"], ts), fw["g"]),
+                 "H": Hn.max_rel(_rows(out["H"], ts), fw["h"]), "dx": Hn.max_rel(_rows(out["dx"], ts), bw["dx"]),
+                 "dU": Hn.max_rel(_rows(out["dU"], ts), bw["dU"])})
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
+    print("d_model 8192, d_ff 65472:", {k: float("%.3g" % v) for k, v in errs.items()})
+    ctx.close()
+
+
 @pytest.mark.parametrize("with_table", [False, True])
 def test_c2_shaped_dense_and_additive_layers_full_size(with_table):
     """The dense SwiGLU layer and the additive variant at the 350M shape, every element of every output
