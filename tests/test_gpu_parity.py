@@ -183,9 +183,16 @@ def test_bf16_dense_swiglu_and_additive_variant(T, d, F, with_table):
 
 
 @pytest.mark.parametrize("T,V", [(1, 1), (2, 2), (64, 5), (4096, 50304), (4097, 128256), (16384, 128256),
-                                 (65536, 128256), (70001, 64), (5000, (1 << 20) + 3)])
+                                 (65536, 128256), (70001, 64), (5000, (1 << 20) + 3), (3000, 2 ** 31 - 1)])
 def test_sort_unique_offsets_bit_exact(T, V):
-    ids = inputs.zipf_ids(T, V, seed=T + V)
+    if V < 1 << 24:
+        ids = inputs.zipf_ids(T, V, seed=T + V)
+    else:   # the largest table an int32 id can address: 31 key bits, both ends of the range, repeated ids
+        rng = np.random.default_rng(T)
+        ids = rng.integers(0, V, T).astype(np.int32)
+        ids[[0, 7, T - 1]] = V - 1
+        ids[[1, 8, T - 2]] = 0
+        ids[100:200] = ids[300:400]
     s = inputs.StemShape("ints", 64, 64, V, 1, T, "bf16")
     ctx = Hn.make_ctx(s, T)
     eg = Hn.hip_embed_grad(ctx, torch.from_numpy(ids).to(DEV), None, V, with_rows=False)
