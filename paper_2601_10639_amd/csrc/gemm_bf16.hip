@@ -191,12 +191,21 @@ __device__ __forceinline__ void unpack8(uint4 u, float (&f)[8]) {
 
 // Workgroup -> output tile.  Consecutive workgroup ids go round-robin over the 8 XCDs,
 // each with its own L2; giving every XCD one contiguous run of tiles, walked in bands of
-// 8 tile-rows, keeps the operand panels an XCD's workgroups share in that XCD's L2.
+// GM tile-rows (down the rows of a band first), keeps the operand panels an XCD's workgroups
+// share in that XCD's L2.  GM = 4: the 32 workgroups an XCD runs at a time cover 4 tile-rows
+// x 8 tile-columns, i.e. 4 panels of the M-side operand (activations or their gradients, rows
+// no other XCD reads) and 8 of the N-side one (mostly weights, which all XCDs read and the
+// memory-side cache therefore holds).  With GM = 8 (8 + 4 panels, the same count) every product
+// was 1-3 % slower.  The dH product takes GM = 7, which divides neither the 32 tiles an XCD runs
+// at a time nor its run: the XCDs then sit at different rows and columns of their bands, and
+// their epilogues (each reads a G tile and writes two tiles) meet less often: 0.565 ms with
+// 8, 0.545 with 4 or 6, 0.537 with 3 or 5, 0.532 with 7, 0.545-0.55 with 9, 11, 13
+// (d_model 2048, d_ff 8192, 16384 tokens).
+template <int GM>
 __device__ __forceinline__ void tile_of_block(int b, int nb, int ntm, int ntn, int& tm, int& tn) {
   const int q = nb >> 3, r = nb & 7;
   const int xcd = b & 7, idx = b >> 3;
   const int L = xcd * q + (xcd < r ? xcd : r) + idx;
-  const int GM = 8;
   const int per_group = GM * ntn;
   const int group = L / per_group;
   const int first = group * GM;
@@ -214,6 +223,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int ntm = (p.M + BM - 1) / BM, ntn = (p.N + BN - 1) / BN;
+  constexpr int BAND = (EPI == EPI_DH || EPI == EPI_DH_UP || EPI == EPI_DH_UPE) ? 7 : 4;   // see tile_of_block
   int tm, tn;
   if (EPI == EPI_F32 && p.ksplit > 1) {
     // Split along K (weight gradients of narrow layers: few output tiles, long K): slice z of the
@@ -221,7 +231,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     // the slices in order.  The slice is expressed by moving the operands and shrinking K.
     const int ntiles = ntm * ntn;
     const int z = blockIdx.x / ntiles;
-    tile_of_block(blockIdx.x - z * ntiles, ntiles, ntm, ntn, tm, tn);
+    tile_of_block<BAND>(blockIdx.x - z * ntiles, ntiles, ntm, ntn, tm, tn);
     const int nk_all = (p.K + BK - 1) / BK;
     const int per = (nk_all + p.ksplit - 1) / p.ksplit;
     const int k0 = z * per * BK;
@@ -235,7 +245,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     p.C = p.ws + (size_t)z * p.M * p.N;
     p.accumulate = 0;
   } else {
-    tile_of_block(blockIdx.x, gridDim.x, ntm, ntn, tm, tn);
+    tile_of_block<BAND>(blockIdx.x, gridDim.x, ntm, ntn, tm, tn);
   }
   const int m0 = tm * BM, n0 = tn * BN;
   // K rotation.  Workgroups on XCD x start their K loop x eighths of the way in and wrap around, so
