@@ -118,13 +118,17 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p) {
     }
   }
   u32x4_t ring[DEPTH][3];
-  int ktile = kt0;   // next K tile to request
+  // The K tiles of the slice are walked from a start that differs from one n tile to the next and
+  // wraps around: at any moment the workgroups then read different stretches of their weight rows
+  // (rows 4 or 16 KB apart, whose lines at one k sit in the same few memory channels).
+  // (16-layer decode step 0.684-0.692 ms against 0.695-0.703 with every workgroup starting at the slice's first tile)
+  int kpos = nk > 1 ? (int)(((long)tn * nk) / p.nt) % nk : 0;
   auto request = [&](u32x4_t(&r)[3]) {
-    const int so = ktile * (SBK * 2);
+    const int so = (kt0 + kpos) * (SBK * 2);
     r[0] = __builtin_amdgcn_raw_buffer_load_b128(ra, goff[0], so, 0);
     r[1] = __builtin_amdgcn_raw_buffer_load_b128(ra, goff[1], so, 0);
     r[2] = __builtin_amdgcn_raw_buffer_load_b128(rb, goff[2], so, 0);
-    ++ktile;
+    if (++kpos >= nk) kpos = 0;
   };
   auto commit = [&](const u32x4_t(&r)[3], int stage) {
     char* st = smem + stage * STAGE;
@@ -156,7 +160,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p) {
   // ---- main loop -----------------------------------------------------------------------------
   // iteration t: tile t+1 goes from registers to its LDS stage, tile t+DEPTH is requested into
   // the registers just freed, barrier, the fragments of tile t+1 are read while the MFMAs of
-  // tile t run.  Requests past the K range read other (valid or zero) bytes that are never used.
+  // tile t run.  Requests past the last tile wrap around to tiles already used; what they bring is never used.
 #pragma unroll
   for (int s = 0; s < DEPTH; ++s) request(ring[s]);
   if (EPI == EPI_GATE) {
