@@ -111,3 +111,31 @@ def test_early_touch_of_gathered_rows_stays_inside_the_table():
                 second = col + 64 if col + 64 < F else col
                 for first_elem in (col, second):
                     assert 0 <= first_elem and first_elem * 2 + 4 <= F * 2, (F, tn, wn, first_elem)
+
+
+def test_tile_map_model_covers_every_tile_once():
+    """The large GEMM maps workgroup ids to output tiles in XCD-major runs walked in bands of tile rows
+    (4, or 7 in the dH product).  Host-side model of that map over ragged and full grids, incl. fewer
+    workgroups than XCDs and band heights that do not divide the number of tile rows: every tile is
+    produced by exactly one workgroup."""
+    def tile_of_block(b, nb, ntm, ntn, gm):
+        q, r = nb >> 3, nb & 7
+        xcd, idx = b & 7, b >> 3
+        lin = xcd * q + min(xcd, r) + idx
+        per_group = gm * ntn
+        group = lin // per_group
+        first = group * gm
+        gsize = min(ntm - first, gm)
+        inside = lin - group * per_group
+        return first + inside % gsize, inside // gsize
+
+    for gm in (4, 7):
+        for ntm in (1, 2, 3, 5, 7, 8, 9, 13, 64):
+            for ntn in (1, 2, 3, 8, 31, 32):
+                nb = ntm * ntn
+                seen = set()
+                for b in range(nb):
+                    tm, tn = tile_of_block(b, nb, ntm, ntn, gm)
+                    assert 0 <= tm < ntm and 0 <= tn < ntn, (gm, ntm, ntn, b, tm, tn)
+                    seen.add((tm, tn))
+                assert len(seen) == nb, (gm, ntm, ntn)
